@@ -1,0 +1,326 @@
+"""Plain fp64 CPU oracle of KV-Runahead's per-chunk hot path.
+
+TEST INFRASTRUCTURE ONLY.  Slow, unblocked, unfused numpy written from the paper's
+statement of the computation; it shares no code with the HIP library, does not import
+it, and must not be called from the product path.
+
+What it defines
+  * causal attention of one layer on one process: softmax of the scaled Q.K^T map
+    with the upper triangle masked to -inf, times V (Fig. 1(b); App. C listing,
+    attention-weights and attention-output steps);
+  * the KV-cache form each KV-Runahead process runs: concatenate the received cache
+    with the local K,V, then attend the local queries to prefix+chunk keys
+    (Sec. 4.1; Fig. 5; App. C listing, cache concatenation steps);
+  * rotary position embedding (not in the paper; it comes from the LLaMA / Falcon
+    models of Sec. 5 and is fixed here as the half-split "rotate-half" pairing);
+  * the dot-product and traffic counts of Sec. 3 / Sec. 4.1 (Eq. 1-6, Fig. 4, Fig. 5);
+  * the context-level load-balancing objective of Sec. 4.2 reduced to per-chunk costs:
+    makespan of a partition, even split, exhaustive search.
+
+Pinned by tests/test_oracle_*.py against hand-computed rationals, closed forms,
+torch's CPU scaled_dot_product_attention, the paper's worked 9-token example and
+brute force.  Parity status: the rotary pairing convention (half-split versus
+interleaved) is unpinned by the paper; everything else is pinned.
+"""
+from __future__ import annotations
+
+import itertools
+import math
+
+import numpy as np
+
+
+# --------------------------------------------------------------------------- bf16 helpers
+def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
+    """Widen bf16 bit patterns (uint16) exactly to float64."""
+    bits = np.asarray(bits, dtype=np.uint16)
+    return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+def f64_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round float64 to the nearest bf16 (ties to even) and return the bit patterns.
+
+    Done on the exact binary expansion of the double: keep 8 significant bits, look at
+    the rest as guard/sticky.  Values are assumed finite and inside bf16's normal range
+    (true for every tensor this repository generates).
+    """
+    x = np.asarray(x, dtype=np.float64)
+    out = np.zeros(x.shape, dtype=np.uint16)
+    nz = x != 0.0
+    m, e = np.frexp(np.abs(x[nz]))           # |x| = m * 2**e, 0.5 <= m < 1
+    sig = m * 256.0                           # 8 significant bits live in [128, 256)
+    lo = np.floor(sig)
+    frac = sig - lo
+    up = (frac > 0.5) | ((frac == 0.5) & (np.mod(lo, 2.0) == 1.0))
+    lo = lo + up
+    carry = lo == 256.0
+    lo = np.where(carry, 128.0, lo)
+    e = e + carry
+    # value = lo * 2**(e-8), lo in [128,256): biased exponent = (e-1)+127, mantissa = lo-128
+    bexp = (e - 1 + 127).astype(np.int64)
+    if np.any(bexp <= 0) or np.any(bexp >= 255):
+        raise ValueError("value outside bf16 normal range")
+    bits = (bexp << 7) | (lo.astype(np.int64) - 128)
+    bits = bits | (np.signbit(x[nz]).astype(np.int64) << 15)
+    out[nz] = bits.astype(np.uint16)
+    out[~nz] = (np.signbit(x[~nz]).astype(np.uint16) << np.uint16(15))
+    return out
+
+
+# --------------------------------------------------------------------------- rotary embedding
+def rope(x: np.ndarray, positions: np.ndarray, base: float) -> np.ndarray:
+    """Rotate x[t, h, :] by the angle set of absolute position positions[t].
+
+    Half-split pairing: component i is paired with component i + d/2, and the pair is
+    turned by phi = position * base**(-2 i / d).  Positions count tokens of the whole
+    context from 0, so row r of a chunk that starts at `prefix` has position prefix + r.
+    """
+    x = np.asarray(x, dtype=np.float64)
+    T, _, d = x.shape
+    half = d // 2
+    inv_freq = np.float64(base) ** (-2.0 * np.arange(half, dtype=np.float64) / d)
+    phi = np.asarray(positions, dtype=np.float64).reshape(T, 1) * inv_freq.reshape(1, half)
+    cos = np.cos(phi)[:, None, :]
+    sin = np.sin(phi)[:, None, :]
+    lo, hi = x[..., :half], x[..., half:]
+    return np.concatenate([lo * cos - hi * sin, hi * cos + lo * sin], axis=-1)
+
+
+# --------------------------------------------------------------------------- attention
+def attention_weights(q: np.ndarray, k: np.ndarray, scale: float, first_pos: int = 0) -> np.ndarray:
+    """softmax(scale * q k^T + mask) for ONE head.
+
+    q: [n, d] queries at absolute positions first_pos .. first_pos+n-1;
+    k: [m, d] keys at absolute positions 0 .. m-1.  Key j is visible to the query at
+    position t iff j <= t; everything else carries -inf before the softmax (Fig. 1(b)).
+    """
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    n, m = q.shape[0], k.shape[0]
+    s = scale * (q @ k.T)
+    t = first_pos + np.arange(n).reshape(n, 1)
+    j = np.arange(m).reshape(1, m)
+    s = np.where(j <= t, s, -np.inf)
+    s = s - s.max(axis=1, keepdims=True)
+    w = np.exp(s)
+    return w / w.sum(axis=1, keepdims=True)
+
+
+def _kv_head(h: int, n_q_heads: int, n_kv_heads: int) -> int:
+    """Query head h reads key/value head floor(h / G), G = n_q_heads / n_kv_heads."""
+    if n_q_heads % n_kv_heads:
+        raise ValueError("n_q_heads must be a multiple of n_kv_heads")
+    return h // (n_q_heads // n_kv_heads)
+
+
+def causal_attention(q, k, v, scale, rope_base=None):
+    """Full-context causal attention of one layer (Fig. 1(b)).
+
+    q: [C, H, d]; k, v: [C, H_kv, d], un-rotated.  With rope_base set, Q and K are
+    rotated by their absolute positions 0..C-1 first (V never is).  Returns [C, H, d].
+    """
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    C, H, d = q.shape
+    Hkv = k.shape[1]
+    if rope_base is not None:
+        pos = np.arange(C)
+        q = rope(q, pos, rope_base)
+        k = rope(k, pos, rope_base)
+    out = np.empty((C, H, d), dtype=np.float64)
+    for h in range(H):
+        g = _kv_head(h, H, Hkv)
+        w = attention_weights(q[:, h, :], k[:, g, :], scale, first_pos=0)
+        out[:, h, :] = w @ v[:, g, :]
+    return out
+
+
+def append_kv(k_cache, v_cache, k, v, prefix_len, rope_base=None, q=None):
+    """Cache population of one chunk (App. C listing: cat(cache, local K/V)).
+
+    k_cache, v_cache: [capacity, H_kv, d] fp64 arrays updated in place on rows
+    [prefix_len, prefix_len + c); k, v: [c, H_kv, d] un-rotated.  K (and q, if given)
+    are rotated by absolute positions prefix_len + r.  Returns the rotated q (or None).
+    """
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    c = k.shape[0]
+    if prefix_len < 0 or prefix_len + c > k_cache.shape[0]:
+        raise ValueError("chunk does not fit the cache")
+    pos = prefix_len + np.arange(c)
+    if rope_base is not None:
+        k = rope(k, pos, rope_base)
+        if q is not None:
+            q = rope(np.asarray(q, dtype=np.float64), pos, rope_base)
+    k_cache[prefix_len:prefix_len + c] = k
+    v_cache[prefix_len:prefix_len + c] = v
+    return q
+
+
+def chunk_attention(q, k_cache, v_cache, prefix_len, chunk_len, scale):
+    """What one KV-Runahead process computes for its chunk (Sec. 4.1, Fig. 5(b)).
+
+    q: [chunk_len, H, d] already rotated; caches hold rows [0, prefix_len+chunk_len).
+    The query at chunk row r sits at absolute position prefix_len + r and sees cache
+    rows 0 .. prefix_len + r.  Returns [chunk_len, H, d], the same shape as q.
+    """
+    q = np.asarray(q, dtype=np.float64)
+    c, H, d = q.shape
+    if c != chunk_len:
+        raise ValueError("q does not match chunk_len")
+    total = prefix_len + chunk_len
+    Hkv = k_cache.shape[1]
+    out = np.empty((c, H, d), dtype=np.float64)
+    for h in range(H):
+        g = _kv_head(h, H, Hkv)
+        w = attention_weights(q[:, h, :], k_cache[:total, g, :], scale, first_pos=prefix_len)
+        out[:, h, :] = w @ v_cache[:total, g, :]
+    return out
+
+
+def chunked_prefill(q, k, v, boundaries, scale, rope_base=None):
+    """Run the chunks of a partition in order: append, then attend (chain p_0 -> p_1 -> ...).
+
+    boundaries: [0 = b_0 < b_1 < ... < b_p = C].  Returns (out [C,H,d], k_cache, v_cache).
+    """
+    q = np.asarray(q, dtype=np.float64)
+    C, H, d = q.shape
+    Hkv = k.shape[1]
+    b = [int(x) for x in boundaries]
+    if b[0] != 0 or b[-1] != C or any(b[i + 1] <= b[i] for i in range(len(b) - 1)):
+        raise ValueError("boundaries must rise strictly from 0 to C")
+    k_cache = np.zeros((C, Hkv, d), dtype=np.float64)
+    v_cache = np.zeros((C, Hkv, d), dtype=np.float64)
+    out = np.empty((C, H, d), dtype=np.float64)
+    for i in range(len(b) - 1):
+        lo, hi = b[i], b[i + 1]
+        qc = append_kv(k_cache, v_cache, k[lo:hi], v[lo:hi], lo, rope_base, q=q[lo:hi])
+        if qc is None:
+            qc = q[lo:hi]
+        out[lo:hi] = chunk_attention(qc, k_cache, v_cache, lo, hi - lo, scale)
+    return out, k_cache, v_cache
+
+
+def attention_rows(q, k, v, rows, scale, rope_base=None):
+    """Full-context causal attention for a list of absolute positions only.
+
+    Same definition as causal_attention, evaluated row by row (each row is independent
+    of the others), so that large contexts can be checked on a sample.
+    q: [C,H,d], k,v: [C,H_kv,d] un-rotated.  Returns [len(rows), H, d].
+    """
+    q = np.asarray(q)
+    k = np.asarray(k)
+    v = np.asarray(v)
+    C, H, d = q.shape
+    Hkv = k.shape[1]
+    rows = [int(r) for r in rows]
+    tmax = max(rows) + 1
+    kk = np.asarray(k[:tmax], dtype=np.float64)
+    vv = np.asarray(v[:tmax], dtype=np.float64)
+    if rope_base is not None:
+        kk = rope(kk, np.arange(tmax), rope_base)
+    out = np.empty((len(rows), H, d), dtype=np.float64)
+    for n, t in enumerate(rows):
+        qt = np.asarray(q[t:t + 1], dtype=np.float64)
+        if rope_base is not None:
+            qt = rope(qt, np.array([t]), rope_base)
+        for h in range(H):
+            g = _kv_head(h, H, Hkv)
+            s = scale * (kk[:t + 1, g, :] @ qt[0, h, :])
+            s = s - s.max()
+            w = np.exp(s)
+            w = w / w.sum()
+            out[n, h, :] = w @ vv[:t + 1, g, :]
+    return out
+
+
+# --------------------------------------------------------------------------- work / traffic model
+def chunk_lengths(boundaries):
+    b = [int(x) for x in boundaries]
+    return [b[i + 1] - b[i] for i in range(len(b) - 1)]
+
+
+def rect_dot_products(boundaries):
+    """Dot products of Q.K^T each process issues as a dense rectangle: c_i * (prefix_i + c_i)
+    (Fig. 5 caption; Sec. 4.1)."""
+    b = [int(x) for x in boundaries]
+    return [(b[i + 1] - b[i]) * b[i + 1] for i in range(len(b) - 1)]
+
+
+def tsp_dot_products(context_len, p):
+    """Tensor/sequence-parallel baseline: every process multiplies its C/p queries by all
+    C keys (Fig. 4 caption)."""
+    if context_len % p:
+        raise ValueError("even split needs p | C")
+    return [(context_len // p) * context_len] * p
+
+
+def useful_pairs(prefix_len, chunk_len):
+    """(query, key) pairs under the causal mask for one chunk, diagonal included."""
+    return chunk_len * prefix_len + chunk_len * (chunk_len + 1) // 2
+
+
+def useful_flops(prefix_len, chunk_len, n_q_heads, head_dim):
+    """2d multiply-adds for Q.K^T plus 2d for P.V per visible pair per head."""
+    return 4 * head_dim * n_q_heads * useful_pairs(prefix_len, chunk_len)
+
+
+def kvr_traffic_entries(boundaries):
+    """(K,V) rows put on the network by the chain p_0 -> p_1 -> ...: process i forwards its
+    whole cache, K rows and V rows counted separately (Fig. 5 caption; Eq. 5-6)."""
+    b = [int(x) for x in boundaries]
+    return 2 * sum(b[1:-1])
+
+
+def tsp_traffic_entries(context_len, p):
+    """all-gather: every process receives the K and V rows of all others (Fig. 4 caption; Eq. 3-4)."""
+    return 2 * (p - 1) * context_len
+
+
+def ttft_lower_bound_ratio(p):
+    """TTFT*(p) / TTFT(1) of Eq. 2."""
+    return 0.5 * (1.0 / p + 1.0 / (p * p))
+
+
+# --------------------------------------------------------------------------- load balancing
+def analytic_cost(prefix_len, chunk_len):
+    """Twice the area under the diagonal of a chunk's rectangle: c * (2 prefix + c)."""
+    return float(chunk_len * (2 * prefix_len + chunk_len))
+
+
+def makespan(boundaries, cost=analytic_cost):
+    """Largest per-chunk cost of a partition: with every chunk on its own worker and many
+    layers, the slowest worker sets the pace (Sec. 4.2, second bullet)."""
+    b = [int(x) for x in boundaries]
+    return max(cost(b[i], b[i + 1] - b[i]) for i in range(len(b) - 1))
+
+
+def equal_split(context_len, p, granularity):
+    """Even partitioning (KVR-E), boundaries rounded to the granularity grid."""
+    g = granularity
+    return [g * int(math.floor(k * context_len / (p * g) + 0.5)) for k in range(p + 1)]
+
+
+def sqrt_rule(context_len, p, granularity):
+    """Continuous optimum of the analytic cost, b_k = C sqrt(k/p), rounded to the grid."""
+    g = granularity
+    return [g * int(math.floor(context_len * math.sqrt(k / p) / g + 0.5)) for k in range(p + 1)]
+
+
+def brute_force_balance(context_len, p, granularity, cost=analytic_cost):
+    """Exhaustive search over all strictly rising boundary tuples on the granularity grid.
+
+    Returns (boundaries, makespan); among equal makespans the lexicographically smallest
+    boundary vector is kept.
+    """
+    if context_len % granularity or context_len < p * granularity:
+        raise ValueError("context does not fit the grid")
+    n = context_len // granularity
+    best, best_b = None, None
+    for cut in itertools.combinations(range(1, n), p - 1):
+        b = [0] + [granularity * x for x in cut] + [context_len]
+        m = makespan(b, cost)
+        if best is None or m < best:
+            best, best_b = m, b
+    return best_b, best
