@@ -1,0 +1,122 @@
+/*
+ * libkvra - single-GPU hot path of KV-Runahead (chunked prefill with a KV-cache) for gfx950.
+ *
+ * The prompt of length C is cut into consecutive chunks c_0..c_{p-1} (Sec. 3).  The worker of
+ * chunk i appends its K,V behind the cache built from chunks 0..i-1 and attends its queries
+ * to prefix+chunk keys; only the diagonal block needs the causal mask (Sec. 4.1, Fig. 2, Fig. 5,
+ * App. C listing).  On one GPU the chunks run as successive launches on one stream.
+ *
+ * Conventions shared by all entry points
+ *   - Plain C ABI.  Every `void*` tensor argument is a DEVICE pointer owned by the caller; the
+ *     library never frees or keeps it.  bf16 = the upper 16 bits of an IEEE float32.
+ *   - Tensors are dense, token-major: [tokens, heads, head_dim], head_dim contiguous.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  GPU entry points
+ *     only enqueue work on it and return; they never synchronise.
+ *   - Return value: KVRA_OK, or a negative code; on error nothing was enqueued.
+ *   - head_dim must be 64 or 128; n_q_heads must be a multiple of n_kv_heads; query head h
+ *     reads key/value head h / (n_q_heads / n_kv_heads).
+ *   - kvra_chunk_attn keeps partial results in a per-device workspace that the library allocates
+ *     on first use and grows on demand (hipMalloc, cached until the process ends); calls that
+ *     overlap on one device from different streams must not share it and are not supported.
+ */
+#ifndef KVRA_H
+#define KVRA_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  KVRA_OK = 0,
+  KVRA_EINVAL = -1,       /* null pointer, non-positive size, heads not divisible, bad scale   */
+  KVRA_EUNSUPPORTED = -2, /* head_dim other than 64 / 128, or a size beyond the 32-bit tiling   */
+  KVRA_ERANGE = -3,       /* prefix_len + chunk_len exceeds the cache capacity                  */
+  KVRA_ELAUNCH = -4,      /* the HIP runtime refused the launch or an allocation                */
+  KVRA_ENODEVICE = -5     /* no usable gfx950 device                                            */
+};
+
+/* Human-readable text for a return code (static storage, never NULL). */
+const char* kvra_strerror(int code);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int kvra_version(void);
+
+/*
+ * Cache population of one chunk: the "K = cat(cache.K, K); V = cat(cache.V, V)" step of the
+ * attention block (App. C listing; Sec. 4.3 asks for the cache to be physically contiguous).
+ * Rotary position embedding is applied on the way (the paper's models, Sec. 5, are rotary;
+ * half-split pairing: component i pairs with i + head_dim/2 and turns by
+ * position * rope_base^(-2i/head_dim), position = prefix_len + row).
+ *
+ *   k_in    [chunk_len, n_kv_heads, head_dim] bf16, un-rotated            (device, read)
+ *   v_in    [chunk_len, n_kv_heads, head_dim] bf16                        (device, read)
+ *   q_inout [chunk_len, n_q_heads,  head_dim] bf16 or NULL; rotated in place (device, read/write)
+ *   k_cache, v_cache [capacity, n_kv_heads, head_dim] bf16; rows [prefix_len, prefix_len+chunk_len)
+ *           are written, every other row is left untouched               (device, write)
+ *   rope_base  e.g. 10000; <= 0 turns the rotation off (K and Q are copied / left as they are)
+ *
+ * Angles are formed in fp64, the rotation in fp32, results rounded to nearest-even bf16.
+ * V is copied bit for bit.  Errors: KVRA_EINVAL, KVRA_EUNSUPPORTED, KVRA_ERANGE, KVRA_ELAUNCH.
+ */
+int kvra_append_kv(const void* k_in, const void* v_in, void* q_inout,
+                   void* k_cache, void* v_cache,
+                   int64_t prefix_len, int64_t chunk_len, int64_t capacity,
+                   int n_q_heads, int n_kv_heads, int head_dim,
+                   float rope_base, void* stream);
+
+/*
+ * Attention of one chunk against prefix+chunk keys: softmax(scale * Q K^T + mask) V with the
+ * mask -inf above the diagonal (Fig. 1(b); Sec. 4.1; App. C listing, weights and output steps).
+ * The query in chunk row r sits at absolute position prefix_len + r and sees cache rows
+ * 0 .. prefix_len + r inclusive.  Tiles wholly above the diagonal are never issued.
+ *
+ *   q        [chunk_len, n_q_heads, head_dim] bf16, already rotated       (device, read)
+ *   k_cache, v_cache  token-major caches, rows [0, prefix_len+chunk_len) valid (device, read)
+ *   scale    multiplies Q K^T before the softmax (1/sqrt(head_dim) by convention); finite, > 0
+ *   out      [chunk_len, n_q_heads, head_dim] bf16                        (device, write)
+ *
+ * bf16 MFMA products with fp32 accumulation, fp32 online softmax, P rounded to bf16 before P V.
+ * Errors: KVRA_EINVAL, KVRA_EUNSUPPORTED, KVRA_ELAUNCH.
+ */
+int kvra_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
+                    int64_t prefix_len, int64_t chunk_len,
+                    int n_q_heads, int n_kv_heads, int head_dim,
+                    float scale, void* out, void* stream);
+
+/*
+ * Context-level load balancing (Sec. 4.2), host only.  Picks boundaries 0 = b_0 < b_1 < ... <
+ * b_n = context_len, all multiples of `granularity`, that minimise the largest per-chunk cost
+ * max_i cost(b_i, b_{i+1} - b_i): with one worker per chunk and many layers the slowest worker
+ * sets the time to first token.  The search is exact over the grid (dynamic programme over
+ * O(n_chunks * (context_len/granularity)^2) cost evaluations); among partitions of equal makespan
+ * the lexicographically smallest boundary vector is returned.
+ *
+ *   cost   called on the host with (prefix_len, chunk_len, user); any unit; NULL selects the
+ *          analytic causal-work model chunk_len * (2*prefix_len + chunk_len)
+ *   boundaries_out  host array of n_chunks + 1 entries
+ *   makespan_out    host double or NULL
+ *
+ * Errors (KVRA_EINVAL): n_chunks < 1, granularity < 1, context_len not a multiple of granularity,
+ * context_len < n_chunks * granularity, NULL boundaries_out, a cost that returns NaN.
+ */
+typedef double (*kvra_cost_fn)(int64_t prefix_len, int64_t chunk_len, void* user);
+
+int kvra_balance(int64_t context_len, int n_chunks, int64_t granularity,
+                 kvra_cost_fn cost, void* user,
+                 int64_t* boundaries_out, double* makespan_out);
+
+/* Even partitioning (the KVR-E variant of Sec. 5): b_k = granularity * round(k*C/(n*granularity)).
+ * Same argument checks as kvra_balance. */
+int kvra_equal_split(int64_t context_len, int n_chunks, int64_t granularity, int64_t* boundaries_out);
+
+/* Largest per-chunk cost of a given partition (same cost convention as kvra_balance).
+ * boundaries: host array of n_chunks + 1 strictly rising entries starting at 0. */
+int kvra_makespan(const int64_t* boundaries, int n_chunks, kvra_cost_fn cost, void* user,
+                  double* makespan_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVRA_H */

@@ -1,0 +1,33 @@
+// Internal declarations shared by the translation units of libkvra (not installed).
+#ifndef KVRA_INTERNAL_H
+#define KVRA_INTERNAL_H
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+
+#include "kvra.h"
+
+namespace kvra {
+
+int launch_append_kv(const void* k_in, const void* v_in, void* q_inout, void* k_cache, void* v_cache,
+                     int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_kv_heads, int head_dim,
+                     float rope_base, hipStream_t stream);
+
+int launch_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
+                      int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_kv_heads, int head_dim,
+                      float scale, void* out, hipStream_t stream);
+
+// Launch with the runtime's own status as the result.  (hipGetLastError would also pick up
+// stale, unrelated codes that other users of the runtime in this thread left behind.)
+template <typename Args>
+inline int launch_kernel(void (*kernel)(Args), dim3 grid, dim3 block, Args& args, hipStream_t stream) {
+  void* params[] = {static_cast<void*>(&args)};
+  const hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, params, 0, stream);
+  return e == hipSuccess ? KVRA_OK : KVRA_ELAUNCH;
+}
+
+}  // namespace kvra
+
+#endif

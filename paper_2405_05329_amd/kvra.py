@@ -1,0 +1,150 @@
+"""ctypes binding of libkvra: the same entry points as include/kvra.h, argument marshalling only.
+
+Tensor arguments may be torch tensors (their data_ptr() is passed; they must live on the GPU and
+be contiguous) or plain integer device addresses.  Every step of the path runs inside the library's
+HIP kernels; there is no Python or CPU fallback: if the shared library is missing, importing this
+module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libkvra.so")
+
+KVRA_OK = 0
+KVRA_EINVAL = -1
+KVRA_EUNSUPPORTED = -2
+KVRA_ERANGE = -3
+KVRA_ELAUNCH = -4
+KVRA_ENODEVICE = -5
+
+COST_FN = ctypes.CFUNCTYPE(ctypes.c_double, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p)
+
+
+class KvraError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {kvra_strerror(code)} ({code})")
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2405_05329_amd.build` "
+            "(there is no fallback path)")
+    # torch owns the device memory and streams handed to the library, so both must talk to ONE HIP
+    # runtime: torch ships its own libamdhip64 (same soname as ROCm's) and must be loaded first,
+    # otherwise the process ends up with two runtimes that do not know each other's allocations.
+    import torch  # noqa: F401
+    lib = ctypes.CDLL(LIB_PATH)
+    i64, i32, f32, vp = ctypes.c_int64, ctypes.c_int, ctypes.c_float, ctypes.c_void_p
+    lib.kvra_strerror.restype = ctypes.c_char_p
+    lib.kvra_strerror.argtypes = [i32]
+    lib.kvra_version.restype = i32
+    lib.kvra_version.argtypes = []
+    lib.kvra_append_kv.restype = i32
+    lib.kvra_append_kv.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, f32, vp]
+    lib.kvra_chunk_attn.restype = i32
+    lib.kvra_chunk_attn.argtypes = [vp, vp, vp, i64, i64, i32, i32, i32, f32, vp, vp]
+    lib.kvra_balance.restype = i32
+    lib.kvra_balance.argtypes = [i64, i32, i64, ctypes.c_void_p, vp, ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)]
+    lib.kvra_equal_split.restype = i32
+    lib.kvra_equal_split.argtypes = [i64, i32, i64, ctypes.POINTER(i64)]
+    lib.kvra_makespan.restype = i32
+    lib.kvra_makespan.argtypes = [ctypes.POINTER(i64), i32, ctypes.c_void_p, vp, ctypes.POINTER(ctypes.c_double)]
+    return lib
+
+
+_lib = _load()
+
+
+def _ptr(x):
+    """Device address of a torch tensor (or pass an int / None through)."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if not x.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    if not x.is_cuda:
+        raise ValueError("tensor must live in GPU memory")
+    return x.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        return None
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream     # torch.cuda.Stream
+
+
+def _cost(cost):
+    if cost is None:
+        return None, None
+    cb = COST_FN(lambda prefix, c, _user: float(cost(prefix, c)))
+    return cb, ctypes.cast(cb, ctypes.c_void_p)
+
+
+def kvra_strerror(code: int) -> str:
+    return _lib.kvra_strerror(int(code)).decode()
+
+
+def kvra_version() -> int:
+    return int(_lib.kvra_version())
+
+
+def kvra_append_kv(k_in, v_in, q_inout, k_cache, v_cache, prefix_len, chunk_len, capacity,
+                   n_q_heads, n_kv_heads, head_dim, rope_base, stream=None, check=True) -> int:
+    rc = _lib.kvra_append_kv(_ptr(k_in), _ptr(v_in), _ptr(q_inout), _ptr(k_cache), _ptr(v_cache),
+                             int(prefix_len), int(chunk_len), int(capacity),
+                             int(n_q_heads), int(n_kv_heads), int(head_dim), float(rope_base),
+                             _stream(stream))
+    if check and rc != KVRA_OK:
+        raise KvraError(rc, "kvra_append_kv")
+    return rc
+
+
+def kvra_chunk_attn(q, k_cache, v_cache, prefix_len, chunk_len, n_q_heads, n_kv_heads, head_dim,
+                    scale, out, stream=None, check=True) -> int:
+    rc = _lib.kvra_chunk_attn(_ptr(q), _ptr(k_cache), _ptr(v_cache), int(prefix_len), int(chunk_len),
+                              int(n_q_heads), int(n_kv_heads), int(head_dim), float(scale),
+                              _ptr(out), _stream(stream))
+    if check and rc != KVRA_OK:
+        raise KvraError(rc, "kvra_chunk_attn")
+    return rc
+
+
+def kvra_balance(context_len, n_chunks, granularity, cost=None):
+    """Returns (boundaries list, makespan).  cost(prefix_len, chunk_len) -> float, or None for the
+    analytic causal-work model."""
+    n = int(n_chunks)
+    out = (ctypes.c_int64 * (max(n, 0) + 1))()
+    mk = ctypes.c_double()
+    cb, cbp = _cost(cost)
+    rc = _lib.kvra_balance(int(context_len), n, int(granularity), cbp, None, out, ctypes.byref(mk))
+    if rc != KVRA_OK:
+        raise KvraError(rc, "kvra_balance")
+    return list(out), mk.value
+
+
+def kvra_equal_split(context_len, n_chunks, granularity):
+    n = int(n_chunks)
+    out = (ctypes.c_int64 * (max(n, 0) + 1))()
+    rc = _lib.kvra_equal_split(int(context_len), n, int(granularity), out)
+    if rc != KVRA_OK:
+        raise KvraError(rc, "kvra_equal_split")
+    return list(out)
+
+
+def kvra_makespan(boundaries, cost=None) -> float:
+    b = [int(x) for x in boundaries]
+    arr = (ctypes.c_int64 * len(b))(*b)
+    mk = ctypes.c_double()
+    cb, cbp = _cost(cost)
+    rc = _lib.kvra_makespan(arr, len(b) - 1, cbp, None, ctypes.byref(mk))
+    if rc != KVRA_OK:
+        raise KvraError(rc, "kvra_makespan")
+    return mk.value

@@ -1,0 +1,147 @@
+"""Host-side checks that run without a GPU: the shared library loads, exports every symbol the
+header declares, rejects bad arguments before touching the device, and kvra_balance agrees with
+the oracle's exhaustive search."""
+import ctypes
+import os
+import random
+import re
+
+import pytest
+
+from oracle import kvra_oracle as orc
+from paper_2405_05329_amd import kvra
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "kvra.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(kvra_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_symbols()
+    assert {"kvra_append_kv", "kvra_chunk_attn", "kvra_balance", "kvra_strerror"} <= set(names)
+    lib = ctypes.CDLL(kvra.LIB_PATH)
+    for name in names:
+        assert hasattr(lib, name), name
+    assert kvra.kvra_version() >= 100
+
+
+def test_binding_has_the_same_names():
+    for name in _declared_symbols():
+        assert callable(getattr(kvra, name)), name
+
+
+def test_strerror():
+    assert kvra.kvra_strerror(0) == "ok"
+    for code in (-1, -2, -3, -4, -5, -99):
+        assert kvra.kvra_strerror(code)
+
+
+def test_append_rejects_bad_arguments_before_any_launch():
+    P = 0x1000  # never dereferenced: validation fails first
+    ok = dict(k_in=P, v_in=P, q_inout=P, k_cache=P, v_cache=P, prefix_len=0, chunk_len=4, capacity=8,
+              n_q_heads=4, n_kv_heads=2, head_dim=64, rope_base=10000.0, check=False)
+    def call(**kw):
+        a = dict(ok); a.update(kw)
+        return kvra.kvra_append_kv(**a)
+    assert call(k_in=None) == kvra.KVRA_EINVAL
+    assert call(v_cache=None) == kvra.KVRA_EINVAL
+    assert call(chunk_len=0) == kvra.KVRA_EINVAL
+    assert call(prefix_len=-1) == kvra.KVRA_EINVAL
+    assert call(n_q_heads=3) == kvra.KVRA_EINVAL
+    assert call(n_kv_heads=0) == kvra.KVRA_EINVAL
+    assert call(head_dim=96) == kvra.KVRA_EUNSUPPORTED
+    assert call(prefix_len=5, chunk_len=4, capacity=8) == kvra.KVRA_ERANGE
+    assert call(rope_base=float("nan")) == kvra.KVRA_EINVAL
+    with pytest.raises(kvra.KvraError):
+        a = dict(ok); a.update(check=True, chunk_len=0)
+        kvra.kvra_append_kv(**a)
+
+
+def test_attn_rejects_bad_arguments_before_any_launch():
+    P = 0x1000
+    ok = dict(q=P, k_cache=P, v_cache=P, prefix_len=0, chunk_len=4, n_q_heads=4, n_kv_heads=2,
+              head_dim=128, scale=0.1, out=P, check=False)
+    def call(**kw):
+        a = dict(ok); a.update(kw)
+        return kvra.kvra_chunk_attn(**a)
+    assert call(q=None) == kvra.KVRA_EINVAL
+    assert call(out=None) == kvra.KVRA_EINVAL
+    assert call(chunk_len=0) == kvra.KVRA_EINVAL
+    assert call(prefix_len=-3) == kvra.KVRA_EINVAL
+    assert call(n_q_heads=5) == kvra.KVRA_EINVAL
+    assert call(head_dim=80) == kvra.KVRA_EUNSUPPORTED
+    assert call(scale=float("nan")) == kvra.KVRA_EINVAL
+    assert call(scale=float("inf")) == kvra.KVRA_EINVAL
+    assert call(scale=0.0) == kvra.KVRA_EINVAL
+
+
+def test_balance_argument_checks():
+    for args in [(100, 0, 4), (100, 2, 0), (100, 2, 3), (8, 3, 4), (0, 1, 1)]:
+        with pytest.raises(kvra.KvraError):
+            kvra.kvra_balance(*args)
+    with pytest.raises(kvra.KvraError):
+        kvra.kvra_balance(64, 2, 8, cost=lambda p, c: float("nan"))
+    with pytest.raises(kvra.KvraError):
+        kvra.kvra_makespan([1, 5, 9])
+    with pytest.raises(kvra.KvraError):
+        kvra.kvra_makespan([0, 5, 5])
+
+
+def test_balance_single_chunk_and_full_grid():
+    assert kvra.kvra_balance(4096, 1, 64) == ([0, 4096], 4096.0 ** 2)
+    b, m = kvra.kvra_balance(8, 8, 1)
+    assert b == list(range(9)) and m == 15.0
+
+
+@pytest.mark.parametrize("C,p,g", [(96, 3, 8), (128, 4, 8), (64, 2, 1), (60, 3, 4), (24, 4, 1), (40, 3, 8)])
+def test_balance_equals_exhaustive_search_analytic(C, p, g):
+    want_b, want_m = orc.brute_force_balance(C, p, g)
+    got_b, got_m = kvra.kvra_balance(C, p, g)
+    assert got_b == want_b          # boundaries bit-exact, ties broken the same way
+    assert got_m == want_m
+    assert kvra.kvra_makespan(got_b) == orc.makespan(got_b)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_balance_equals_exhaustive_search_arbitrary_costs(seed):
+    rnd = random.Random(seed)
+    table = {}
+    def cost(prefix, c):
+        # deterministic, non-monotone, many ties
+        if (prefix, c) not in table:
+            table[(prefix, c)] = rnd.choice([1.0, 2.0, 3.0, 5.0]) * c + 0.25 * prefix
+        return table[(prefix, c)]
+    for C, p, g in [(48, 3, 4), (36, 4, 3), (20, 2, 1), (30, 5, 2)]:
+        want_b, want_m = orc.brute_force_balance(C, p, g, cost)
+        got_b, got_m = kvra.kvra_balance(C, p, g, cost)
+        assert got_m == want_m
+        assert got_b == want_b
+        assert kvra.kvra_makespan(got_b, cost) == want_m
+
+
+def test_balance_closed_form_and_bounds():
+    # analytic cost on a fine grid: optimum sits at C sqrt(k/p) (two chunks: C / sqrt 2)
+    b, m = kvra.kvra_balance(4096, 2, 1)
+    assert abs(b[1] - 4096 / 2 ** 0.5) <= 1
+    for C, p, g in [(16384, 8, 64), (8192, 4, 64), (32768, 8, 64)]:
+        b, m = kvra.kvra_balance(C, p, g)
+        sq = orc.sqrt_rule(C, p, g)
+        assert m <= orc.makespan(sq)                 # exact search is at least as good as the rounded rule
+        assert m >= C * C / p                        # and cannot beat the mean
+        assert all(abs(x - y) <= 2 * g for x, y in zip(b, sq))
+        sizes = orc.chunk_lengths(b)
+        assert all(sizes[i] >= sizes[i + 1] - g for i in range(p - 1))
+        eq = kvra.kvra_equal_split(C, p, g)
+        assert eq == orc.equal_split(C, p, g)
+        assert kvra.kvra_makespan(eq) / (C * C / p) == (2 * p - 1) / p
+        # lower bound of Eq. 2 is for whole rectangles; the trapezoid model's bound is the mean
+        assert m / (C * C) < 1.06 / p
+
+
+def test_equal_split_matches_oracle_rounding():
+    for C, p, g in [(256, 3, 64), (4096, 4, 64), (960, 7, 64), (100, 3, 1)]:
+        assert kvra.kvra_equal_split(C, p, g) == orc.equal_split(C, p, g)
