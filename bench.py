@@ -29,14 +29,14 @@ WORKLOAD = "llama7b_16k_balanced"
 
 # HBM bytes per chunk-attention launch (mean over the 8 launches of a step) from
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, see profiles/; None until measured.
-ATTN_TRAFFIC_BYTES = None
+ATTN_TRAFFIC_BYTES = 3.748e8
 
 
 def useful_flops(prefix, c, H, d):
     return 4 * d * H * (c * prefix + c * (c + 1) // 2)
 
 
-def cpu_baseline(cfg, sample_heads=2):
+def cpu_baseline(cfg, sample_heads=8):
     """Times the oracle, as it stands, on a bounded sample: full 16k context, first `sample_heads`
     query heads (and their kv heads)."""
     from oracle import kvra_oracle as orc
@@ -71,6 +71,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the equal-split comparison runs")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also issue one plain 256 MiB device-to-device copy (outside the timed region) so "
+                         "that a rocprofv3 --pmc run holds a dispatch of known traffic to scale counters by")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures the single-GPU hot path only; run with --gpus 1 "
@@ -120,6 +123,13 @@ def main():
     def new_events(n):
         return [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n)]
 
+    if args.calib_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        src.fill_(1)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for s in range(args.warmup):
         run_step(bounds, q_work[s % n_buf])
     torch.cuda.synchronize()
