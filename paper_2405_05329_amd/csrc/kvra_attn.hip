@@ -13,7 +13,15 @@
 // are folded into the row index: virtual row v = token * G + head_in_group.  One K/V tile in LDS
 // then serves several query heads, and the diagonal band (the only masked part) stays one key
 // tile wide whatever G is.
+//
+// Schedule.  A workgroup is 8 waves = two groups of 4 (one wave of each group per SIMD).  Per key
+// tile a wave runs an MFMA block (P.V of the previous tile, then K.Q^T of this one: 32 MFMAs at
+// d = 128) and a VALU block (softmax of this tile, staging of future K/V tiles), with a workgroup
+// barrier after each block.  The second group starts one barrier late, so while one group keeps
+// the matrix pipe busy its SIMD partner does exp2/max/sum on the vector ALU ("ping-pong").
 #include "kvra_internal.h"
+
+#include <type_traits>
 
 namespace kvra {
 
@@ -24,6 +32,14 @@ typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) const void gbl_void;
+
+constexpr int kWaves = 8;              // waves per workgroup
+constexpr int kThreads = 64 * kWaves;
+constexpr int kBN = 64;                // keys per tile
+constexpr int kStages = 3;             // LDS ring depth for K and for V tiles
+constexpr float kRescaleSlack = 8.0f;  // exponent headroom (log2) before the running max is moved
 
 struct AttnArgs {
   const __bf16* q;
@@ -35,8 +51,9 @@ struct AttnArgs {
   int H;
   int Hkv;
   int G;
-  int nq_tiles;
-  float c_log2;   // scale * log2(e): softmax runs in base 2
+  int nq_tiles;      // row tiles per kv head
+  int rows_per_wg;   // virtual rows per workgroup: 32 * (active waves), <= 256
+  float c_log2;      // scale * log2(e): softmax runs in base 2
 };
 
 __device__ __forceinline__ float other_half(float x) {
@@ -45,23 +62,38 @@ __device__ __forceinline__ float other_half(float x) {
   return __uint_as_float((threadIdx.x & 32) ? r[0] : r[1]);
 }
 
-template <int D, int NW>
-__global__ __launch_bounds__(64 * NW, 2) void chunk_attn_kernel(AttnArgs a) {
-  constexpr int BM = 32 * NW;              // virtual rows per workgroup
-  constexpr int BN = 64;                   // keys per tile
+// 64 lanes x 16 bytes from global memory straight into 1 KiB of consecutive LDS starting at
+// lds_byte_addr (lane l lands at +16 l).  Global address = uniform base + per-lane byte offset.
+// Written as inline assembly on purpose: the compiler guards every LDS-direct load it knows about
+// with a full vmcnt(0) wait (it cannot tell the ring slots apart), which would serialise the
+// prefetch; here completion is awaited by hand, once per block, with s_waitcnt vmcnt(n).
+__device__ __forceinline__ void lds_dma16(const void* uniform_base, unsigned lane_byte_off, unsigned lds_byte_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(lane_byte_off), "s"(uniform_base), "s"(lds_byte_addr)
+               : "memory", "m0");
+}
+
+template <int D>
+__global__ __launch_bounds__(kThreads, 1) void chunk_attn_kernel(AttnArgs a) {
+  constexpr int BN = kBN;
   constexpr int CPR = D / 8;               // 16-byte pieces per K/V row
   constexpr int KS = D / 16;               // contraction steps of S^T = K Q^T
   constexpr int DB = D / 32;               // 32-row blocks of O^T
   constexpr int RPB = 256 / (D * 2);       // rows per 256-byte LDS bank span
   constexpr int TILE = BN * CPR;           // 16-byte pieces per tile
-  constexpr int LOADS = TILE / (64 * NW);  // pieces each thread moves per tile
-  static_assert(TILE % (64 * NW) == 0, "tile must split evenly over the workgroup");
+  constexpr int LOADS = TILE / kThreads;   // pieces each thread moves per tile
+  constexpr int PF = 4;                    // LDS operand reads kept in flight ahead of the MFMAs
+  static_assert(TILE % kThreads == 0, "tile must split evenly over the workgroup");
 
-  __shared__ u32x4 ldsK[2][TILE];
-  __shared__ u32x4 ldsV[2][TILE];
+  extern __shared__ u32x4 smem[];          // K ring then V ring, kStages tiles each
+  auto ldsK = [&](int b) -> u32x4* { return smem + b * TILE; };
+  auto ldsV = [&](int b) -> u32x4* { return smem + (kStages + b) * TILE; };
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction
   const int n = lane & 31, kg = lane >> 5;
+  const int phase = wave >> 2;             // 0: first group, 1: second group (one barrier late)
 
   // workgroup -> (kv head, row tile): longest row tiles first; with Hkv a multiple of 8 the
   // heads are dealt to the 8 XCDs (workgroup ids go round-robin over XCDs) so that each
@@ -81,18 +113,20 @@ __global__ __launch_bounds__(64 * NW, 2) void chunk_attn_kernel(AttnArgs a) {
 
   const int VR = a.chunk * a.G;            // virtual rows of this kv head
   const int total = a.prefix + a.chunk;    // valid cache rows
-  const int v0 = qt * BM + wave * 32;
-  const bool wave_active = v0 < VR;
+  const int row_lo = qt * a.rows_per_wg;
+  const int row_hi = min(row_lo + a.rows_per_wg, VR);   // exclusive
+  const int v0 = row_lo + wave * 32;
+  const bool wave_active = v0 < row_hi;
   int vr = v0 + n;
-  const bool row_valid = vr < VR;
-  if (!row_valid) vr = VR - 1;
+  const bool row_valid = vr < row_hi;
+  if (!row_valid) vr = row_hi - 1;
   const int r = vr / a.G;
   const int h = g * a.G + (vr - r * a.G);
   const int qpos = a.prefix + r;
-  const int wmin = a.prefix + min(v0, VR - 1) / a.G;        // wave-uniform
-  const int wmax = a.prefix + min(v0 + 31, VR - 1) / a.G;   // wave-uniform
-  const int kmax = a.prefix + min(qt * BM + BM - 1, VR - 1) / a.G;
-  const int nt = kmax / BN + 1;            // key tiles this workgroup walks
+  const int wmin = a.prefix + min(v0, row_hi - 1) / a.G;        // wave-uniform
+  const int wmax = a.prefix + min(v0 + 31, row_hi - 1) / a.G;   // wave-uniform
+  const int nt = (a.prefix + (row_hi - 1) / a.G) / BN + 1;      // key tiles this workgroup walks
+  const int jw = wave_active ? wmax / BN + 1 : 0;               // key tiles this wave needs
 
   // Q fragment: B operand of S^T, lane (n, kg) holds Q[row n][16 ks + 8 kg .. +7]
   bf16x8 qf[KS];
@@ -102,32 +136,49 @@ __global__ __launch_bounds__(64 * NW, 2) void chunk_attn_kernel(AttnArgs a) {
     for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qrow + 16 * ks + 8 * kg);
   }
 
-  // ---- global -> register -> LDS staging of K/V tiles -------------------------------------
-  u32x4 kr[LOADS], vr4[LOADS];
-  auto gload = [&](int kt) {
+  // ---- global -> LDS staging of K/V tiles (LDS-direct loads, no registers in between) ---------
+  // One wave instruction moves 64 x 16 bytes into 1 KiB of consecutive LDS; lane l lands at
+  // base + 16 l.  Piece p of a tile = (row p / CPR, slot p % CPR); the XOR swizzles that keep the
+  // MFMA operand reads free of bank conflicts are applied on the global side: the lane that owns
+  // slot (row, slot) fetches column piece  slot ^ f(row)  of that row.
+  //   K is read 16 bytes per lane down 16+ consecutive rows of one column piece;
+  //   V is read (transposing) 8 bytes per lane over 4 consecutive rows x 64 bytes.
+  int ld_row[LOADS];
+  unsigned ld_kcc[LOADS], ld_vcc[LOADS], koff[LOADS], voff[LOADS];
+  const unsigned row_stride = static_cast<unsigned>(a.Hkv) * D;   // elements between cache rows
+#pragma unroll
+  for (int i = 0; i < LOADS; ++i) {
+    const int p = (i * kWaves + wave) * 64 + lane;
+    ld_row[i] = p / CPR;
+    const int slot = p % CPR;
+    ld_kcc[i] = static_cast<unsigned>(slot ^ ((ld_row[i] / RPB) % CPR)) * 8;
+    ld_vcc[i] = static_cast<unsigned>(slot ^ (4 * ((ld_row[i] / RPB) % (D / 32)))) * 8;
+    koff[i] = 2u * (static_cast<unsigned>(ld_row[i]) * row_stride + ld_kcc[i]);   // bytes
+    voff[i] = 2u * (static_cast<unsigned>(ld_row[i]) * row_stride + ld_vcc[i]);
+  }
+  const __bf16* kbase = a.k + static_cast<long long>(g) * D;
+  const __bf16* vbase = a.v + static_cast<long long>(g) * D;
+
+  // tile kt of K (or V) -> ring slot buf; rows past the end of the cache repeat the last valid row
+  auto dma_tile = [&](const __bf16* head_base, const unsigned (&off)[LOADS], const unsigned (&cc)[LOADS],
+                      int kt, u32x4* dst) {
+    const __bf16* base = head_base + static_cast<long long>(kt) * BN * row_stride;
+    const int lim = total - 1 - kt * BN;
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
-      const int cid = tid + i * 64 * NW;
-      const int row = cid / CPR, cc = cid % CPR;
-      const int key = min(kt * BN + row, total - 1);   // rows past the end repeat the last valid row
-      const long long off = (static_cast<long long>(key) * a.Hkv + g) * D + cc * 8;
-      kr[i] = *reinterpret_cast<const u32x4*>(a.k + off);
-      vr4[i] = *reinterpret_cast<const u32x4*>(a.v + off);
+      const unsigned o32 = (lim >= BN - 1) ? off[i]
+                                           : 2u * (static_cast<unsigned>(min(ld_row[i], lim)) * row_stride + cc[i]);
+      const unsigned lds_addr = static_cast<unsigned>(reinterpret_cast<uintptr_t>(
+          (lds_void*)(dst + (i * kWaves + wave) * 64)));
+      lds_dma16(base, o32, lds_addr);
     }
   };
-  auto lstore = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < LOADS; ++i) {
-      const int cid = tid + i * 64 * NW;
-      const int row = cid / CPR, cc = cid % CPR;
-      // XOR swizzles keep the MFMA operand reads below free of bank conflicts:
-      //   K is read 16 bytes per lane down 16+ consecutive rows of one column piece;
-      //   V is read (transposing) 8 bytes per lane over 4 consecutive rows x 64 bytes.
-      const int kslot = cc ^ ((row / RPB) % CPR);
-      const int vslot = cc ^ (4 * ((row / RPB) % (D / 32)));
-      ldsK[buf][row * CPR + kslot] = kr[i];
-      ldsV[buf][row * CPR + vslot] = vr4[i];
-    }
+  // staging step s moves K tile s+1 and V tile s; returns the number of loads it issued
+  auto stage = [&](int s) -> int {
+    int cnt = 0;
+    if (s + 1 < nt) { dma_tile(kbase, koff, ld_kcc, s + 1, ldsK((s + 1) % kStages)); cnt += LOADS; }
+    if (s < nt) { dma_tile(vbase, voff, ld_vcc, s, ldsV(s % kStages)); cnt += LOADS; }
+    return cnt;
   };
 
   f32x16 o[DB];
@@ -135,7 +186,7 @@ __global__ __launch_bounds__(64 * NW, 2) void chunk_attn_kernel(AttnArgs a) {
   for (int db = 0; db < DB; ++db)
 #pragma unroll
     for (int e = 0; e < 16; ++e) o[db][e] = 0.0f;
-  float m = -INFINITY;   // running row max, already multiplied by c_log2
+  float m = -INFINITY;   // exponent reference of the row (scaled by c_log2); >= running max - slack
   float l = 0.0f;        // running row sum of this lane's half of the keys
   const float c = a.c_log2;
 
@@ -147,90 +198,146 @@ __global__ __launch_bounds__(64 * NW, 2) void chunk_attn_kernel(AttnArgs a) {
   const int v_cc0 = 2 * vmh + ((vi & 3) >> 1);            // + 4 db
   const int v_sub = (vi & 1) * 4;                         // element offset inside the 16-byte piece
 
-  gload(0);
-  lstore(0);
+  // ---- prologue: K tiles 0..2 and V tiles 0..1 on their way into LDS -----------------------------
+  // the first MFMA block multiplies a zero P by the ring slot "before" V tile 0: make it finite
+  for (int i = tid; i < TILE; i += kThreads) ldsV(kStages - 1)[i] = u32x4{0u, 0u, 0u, 0u};
+  dma_tile(kbase, koff, ld_kcc, 0, ldsK(0));
+  stage(0);
+  stage(1);
+  // every load so far (the Q fragment included) is drained here: a load left pending across the
+  // loop entry would make the compiler guard the loop's MFMAs with vmcnt waits
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
   __syncthreads();
+  if (phase == 1) __syncthreads();   // second group runs one barrier behind the first
 
-  for (int kt = 0; kt < nt; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < nt) gload(kt + 1);
+  f32x16 s[2];
+  bf16x8 pf[2][2];
+#pragma unroll
+  for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+    for (int si = 0; si < 2; ++si)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) pf[mb][si][e] = static_cast<__bf16>(0.0f);
 
-    if (wave_active && kt * BN <= wmax) {
-      // ---- S^T = K Q^T ---------------------------------------------------------------------
-      f32x16 s[2];
+  // One tile step; RS = j % kStages is a compile-time value so that every LDS operand address is
+  // a loop-invariant per-lane register plus an immediate.
+  auto tile_step = [&](const int j, auto rs_tag) {
+    constexpr int RS = decltype(rs_tag)::value;
+    // ================= MFMA block =================
+    // P.V of tile j-1 followed by K.Q^T of tile j as ONE software-pipelined stream of operand reads
+    // and MFMAs: the LDS read of op i + PF is issued before the MFMA of op i, and the compiler is
+    // told not to move anything across the steps.  The block runs whole for j <= jw: at j = 0 the
+    // P fragment is zero and the "previous" V slot was zero-filled, at j = jw the scores it forms
+    // are never looked at (the price is one tile's worth of MFMAs per wave, the gain is a single
+    // straight-line block).
+    if (j <= jw) {
+      const short* Vb = reinterpret_cast<const short*>(ldsV((RS + kStages - 1) % kStages));
+      const bf16x8* Kb = reinterpret_cast<const bf16x8*>(ldsK(RS));
+      // contraction slot 4e + t of P.V step (mb, si) is key 32 mb + 16 si + 8 e + 4 kg + t on both operands
+      auto vread = [&](int idx) -> bf16x8 {
+        const int mb = idx / (2 * DB), si = (idx / DB) % 2, db = idx % DB;
+        s16x8 vf;
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          const int row = 32 * mb + 16 * si + 8 * e + v_row0;
+          const int slot = (4 * db + v_cc0) ^ v_sw;
+          const short* p = Vb + (row * CPR + slot) * 8 + v_sub;
+          const s16x4 t = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
+          vf[4 * e + 0] = t[0]; vf[4 * e + 1] = t[1]; vf[4 * e + 2] = t[2]; vf[4 * e + 3] = t[3];
+        }
+        return __builtin_bit_cast(bf16x8, vf);
+      };
+      auto kread = [&](int idx) -> bf16x8 {
+        const int ks = idx / 2, mb = idx % 2;
+        return Kb[(32 * mb + n) * CPR + ((2 * ks + kg) ^ k_sw)];
+      };
+      constexpr int N0 = 4 * DB, N = N0 + 2 * KS;
+      auto frag = [&](int i) -> bf16x8 { return (i < N0) ? vread(i) : kread(i - N0); };
+      bf16x8 fq[PF];
+#pragma unroll
+      for (int i = 0; i < PF; ++i) fq[i] = frag(i);
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
         for (int e = 0; e < 16; ++e) s[mb][e] = 0.0f;
-      const bf16x8* Kb = reinterpret_cast<const bf16x8*>(ldsK[buf]);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb) {
-          const int row = 32 * mb + n;
-          const bf16x8 kf = Kb[row * CPR + ((2 * ks + kg) ^ k_sw)];
-          s[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[mb], 0, 0, 0);
+      for (int i = 0; i < N; ++i) {
+        const bf16x8 cur = fq[i % PF];
+        if (i + PF < N) fq[i % PF] = frag(i + PF);
+        if (i < N0) {
+          const int mb = i / (2 * DB), si = (i / DB) % 2, db = i % DB;
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, pf[mb][si], o[db], 0, 0, 0);
+        } else {
+          const int q = i - N0;
+          s[q % 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, qf[q / 2], s[q % 2], 0, 0, 0);
         }
+        __builtin_amdgcn_sched_barrier(0);
       }
-      // register e of block mb is key  kt*BN + 32 mb + 8 (e/4) + 4 kg + e%4  of query n
-      if (kt * BN + BN - 1 > wmin) {
-        const int rel = qpos - kt * BN - 4 * kg;   // key offset (within tile, minus 4kg) still visible
+    }
+    __syncthreads();
+
+    // ================= VALU block =================
+    // staging: this wave's step is j + phase (the late group is one tile ahead in tile numbers);
+    // tiles K(st+2), V(st+1) start their trip now and are awaited one period later
+    const int st = j + phase;
+    const int issued = (st >= 1) ? stage(st + 1) : 0;
+    if (j < jw) {
+      // register e of block mb is key  j*BN + 32 mb + 8 (e/4) + 4 kg + e%4  of query n
+      if (j * BN + BN - 1 > wmin) {
+        int rel = qpos - j * BN - 4 * kg;   // largest still-visible key offset (minus 4 kg)
+        // opaque to the optimiser: otherwise the 32 compares below become 32 loop-carried
+        // counters that are kept up to date (and kept in registers) on every tile
+        asm volatile("" : "+v"(rel));
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
           for (int e = 0; e < 16; ++e)
             if (32 * mb + 8 * (e / 4) + (e % 4) > rel) s[mb][e] = -INFINITY;
       }
-      // ---- online softmax (base 2) ---------------------------------------------------------
+      // ---- online softmax (base 2) with a lazily moved exponent reference -------------------
       float tmax = s[0][0];
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
         for (int e = 0; e < 16; ++e) tmax = fmaxf(tmax, s[mb][e]);
-      tmax = fmaxf(tmax, other_half(tmax));
-      const float mnew = fmaxf(m, tmax * c);
-      const float alpha = __builtin_amdgcn_exp2f(m - mnew);
+      tmax = fmaxf(tmax, other_half(tmax)) * c;
+      // p = exp2(s c - m) stays <= 2^slack as long as the tile max is within the slack of m;
+      // only when some row of the wave outgrows it are m, l and O re-based (wave-uniform branch)
+      if (__builtin_amdgcn_ballot_w64(tmax > m + kRescaleSlack) != 0) {
+        const float mnew = fmaxf(m, tmax);
+        const float alpha = __builtin_amdgcn_exp2f(m - mnew);
+        l *= alpha;
+        m = mnew;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) o[db][e] *= alpha;
+      }
       float psum = 0.0f;
-      bf16x8 pf[2][2];
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          const float p = __builtin_amdgcn_exp2f(fmaf(s[mb][e], c, -mnew));
+          const float p = __builtin_amdgcn_exp2f(fmaf(s[mb][e], c, -m));
           psum += p;
           pf[mb][e / 8][e % 8] = static_cast<__bf16>(p);
         }
-      l = fmaf(l, alpha, psum);
-      m = mnew;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) o[db][e] *= alpha;
-      // ---- O^T += V^T P^T ------------------------------------------------------------------
-      // contraction slot 4e + j of step (mb, si) is key 32 mb + 16 si + 8 e + 4 kg + j on both operands
-      const short* Vb = reinterpret_cast<const short*>(ldsV[buf]);
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int si = 0; si < 2; ++si)
-#pragma unroll
-          for (int db = 0; db < DB; ++db) {
-            s16x8 vf;
-#pragma unroll
-            for (int e = 0; e < 2; ++e) {
-              const int row = 32 * mb + 16 * si + 8 * e + v_row0;
-              const int slot = (4 * db + v_cc0) ^ v_sw;
-              const short* p = Vb + (row * CPR + slot) * 8 + v_sub;
-              const s16x4 t = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
-              vf[4 * e + 0] = t[0]; vf[4 * e + 1] = t[1]; vf[4 * e + 2] = t[2]; vf[4 * e + 3] = t[3];
-            }
-            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf), pf[mb][si], o[db], 0, 0, 0);
-          }
+      l += psum;
     }
-
-    if (kt + 1 < nt) lstore(buf ^ 1);
+    // everything issued before this block (tiles K(st+1), V(st)) must have landed before the barrier
+    if (issued == 2 * LOADS) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * LOADS));
+    else if (issued == LOADS) __builtin_amdgcn_s_waitcnt(0x0F70 | LOADS);
+    else __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
+  };
+  for (int j0 = 0; j0 <= nt; j0 += kStages) {
+    tile_step(j0, std::integral_constant<int, 0>{});
+    if (j0 + 1 <= nt) tile_step(j0 + 1, std::integral_constant<int, 1>{});
+    if (j0 + 2 <= nt) tile_step(j0 + 2, std::integral_constant<int, 2>{});
   }
+  static_assert(kStages == 3, "the unrolled loop above is written for a ring of three");
+  if (phase == 0) __syncthreads();   // both groups execute the same number of barriers
 
   // ---- epilogue: O / l, bf16, store -----------------------------------------------------------
   const float lsum = l + other_half(l);
@@ -243,7 +350,7 @@ __global__ __launch_bounds__(64 * NW, 2) void chunk_attn_kernel(AttnArgs a) {
       for (int r4 = 0; r4 < 4; ++r4) {
         bf16x4 w;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) w[j] = static_cast<__bf16>(o[db][4 * r4 + j] * inv);
+        for (int t = 0; t < 4; ++t) w[t] = static_cast<__bf16>(o[db][4 * r4 + t] * inv);
         *reinterpret_cast<bf16x4*>(orow + 32 * db + 8 * r4 + 4 * kg) = w;
       }
   }
@@ -252,8 +359,6 @@ __global__ __launch_bounds__(64 * NW, 2) void chunk_attn_kernel(AttnArgs a) {
 int launch_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
                       int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_kv_heads, int head_dim,
                       float scale, void* out, hipStream_t stream) {
-  constexpr int NW = 4;
-  constexpr int BM = 32 * NW;
   const int G = n_q_heads / n_kv_heads;
   const int64_t vrows = chunk_len * G;
   if (vrows > (int64_t(1) << 30) || prefix_len + chunk_len > (int64_t(1) << 30)) return KVRA_EUNSUPPORTED;
@@ -267,13 +372,19 @@ int launch_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
   a.H = n_q_heads;
   a.Hkv = n_kv_heads;
   a.G = G;
-  a.nq_tiles = static_cast<int>((vrows + BM - 1) / BM);
+  // spread the 32-row wave slices evenly over the row tiles (e.g. 34 slices -> 5 tiles of 7)
+  const int64_t slices = (vrows + 31) / 32;
+  const int64_t tiles = (slices + kWaves - 1) / kWaves;
+  const int64_t slices_per_tile = (slices + tiles - 1) / tiles;
+  a.nq_tiles = static_cast<int>(tiles);
+  a.rows_per_wg = static_cast<int>(32 * slices_per_tile);
   a.c_log2 = scale * 1.4426950408889634f;
-  const int64_t grid = static_cast<int64_t>(a.nq_tiles) * n_kv_heads;
+  const int64_t grid = tiles * n_kv_heads;
   if (grid > 0x7FFFFFFF) return KVRA_EUNSUPPORTED;
-  const dim3 g3(static_cast<unsigned>(grid)), b3(64 * NW);
-  if (head_dim == 128) return launch_kernel(chunk_attn_kernel<128, NW>, g3, b3, a, stream);
-  return launch_kernel(chunk_attn_kernel<64, NW>, g3, b3, a, stream);
+  const dim3 g3(static_cast<unsigned>(grid)), b3(kThreads);
+  const unsigned smem = 2u * kStages * kBN * static_cast<unsigned>(head_dim) * 2u;   // K ring + V ring
+  if (head_dim == 128) return launch_kernel(chunk_attn_kernel<128>, g3, b3, a, stream, smem);
+  return launch_kernel(chunk_attn_kernel<64>, g3, b3, a, stream, smem);
 }
 
 }  // namespace kvra

@@ -22,9 +22,18 @@ int launch_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
 // Launch with the runtime's own status as the result.  (hipGetLastError would also pick up
 // stale, unrelated codes that other users of the runtime in this thread left behind.)
 template <typename Args>
-inline int launch_kernel(void (*kernel)(Args), dim3 grid, dim3 block, Args& args, hipStream_t stream) {
+inline int launch_kernel(void (*kernel)(Args), dim3 grid, dim3 block, Args& args, hipStream_t stream,
+                         unsigned dynamic_lds_bytes = 0) {
+  if (dynamic_lds_bytes > 64 * 1024) {
+    // more than 64 KiB of dynamic LDS has to be granted per kernel (once per device is enough,
+    // the call is cheap and idempotent)
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            static_cast<int>(dynamic_lds_bytes)) != hipSuccess)
+      return KVRA_ELAUNCH;
+  }
   void* params[] = {static_cast<void*>(&args)};
-  const hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, params, 0, stream);
+  const hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, params,
+                                       dynamic_lds_bytes, stream);
   return e == hipSuccess ? KVRA_OK : KVRA_ELAUNCH;
 }
 
