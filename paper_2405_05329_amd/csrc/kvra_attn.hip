@@ -16,11 +16,9 @@
 //
 // Schedule.  A workgroup is 8 waves = two groups of 4 (one wave of each group per SIMD).  Per key
 // tile a wave runs an MFMA block (P.V of the previous tile, then K.Q^T of this one: 32 MFMAs at
-// d = 128) and a VALU block (softmax of this tile), with a workgroup barrier after each block.
-// The second group starts one barrier late, so while one group keeps the matrix pipe busy its
-// SIMD partner does exp2/max/sum on the vector ALU ("ping-pong").  K/V tiles travel from global
-// memory straight into a three-deep LDS ring (LDS-direct loads issued in the shadow of the MFMAs,
-// two tiles ahead of their use).
+// d = 128) and a VALU block (softmax of this tile, staging of future K/V tiles), with a workgroup
+// barrier after each block.  The second group starts one barrier late, so while one group keeps
+// the matrix pipe busy its SIMD partner does exp2/max/sum on the vector ALU ("ping-pong").
 #include "kvra_internal.h"
 
 #include <type_traits>
@@ -29,7 +27,6 @@ namespace kvra {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -86,7 +83,7 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_attn_kernel(AttnArgs a) {
   constexpr int RPB = 256 / (D * 2);       // rows per 256-byte LDS bank span
   constexpr int TILE = BN * CPR;           // 16-byte pieces per tile
   constexpr int LOADS = TILE / kThreads;   // pieces each thread moves per tile
-  constexpr int PF = 6;                    // LDS operand reads kept in flight ahead of the MFMAs
+  constexpr int PF = 4;                    // LDS operand reads kept in flight ahead of the MFMAs
   static_assert(TILE % kThreads == 0, "tile must split evenly over the workgroup");
 
   extern __shared__ u32x4 smem[];          // K ring then V ring, kStages tiles each
@@ -147,7 +144,7 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_attn_kernel(AttnArgs a) {
   //   K is read 16 bytes per lane down 16+ consecutive rows of one column piece;
   //   V is read (transposing) 8 bytes per lane over 4 consecutive rows x 64 bytes.
   int ld_row[LOADS];
-  unsigned ld_kcc[LOADS], ld_vcc[LOADS];
+  unsigned ld_kcc[LOADS], ld_vcc[LOADS], koff[LOADS], voff[LOADS];
   const unsigned row_stride = static_cast<unsigned>(a.Hkv) * D;   // elements between cache rows
 #pragma unroll
   for (int i = 0; i < LOADS; ++i) {
@@ -156,27 +153,32 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_attn_kernel(AttnArgs a) {
     const int slot = p % CPR;
     ld_kcc[i] = static_cast<unsigned>(slot ^ ((ld_row[i] / RPB) % CPR)) * 8;
     ld_vcc[i] = static_cast<unsigned>(slot ^ (4 * ((ld_row[i] / RPB) % (D / 32)))) * 8;
+    koff[i] = 2u * (static_cast<unsigned>(ld_row[i]) * row_stride + ld_kcc[i]);   // bytes
+    voff[i] = 2u * (static_cast<unsigned>(ld_row[i]) * row_stride + ld_vcc[i]);
   }
   const __bf16* kbase = a.k + static_cast<long long>(g) * D;
   const __bf16* vbase = a.v + static_cast<long long>(g) * D;
 
-  // load i (of LOADS) of tile kt of K (or V) -> ring slot dst; branch-free: a tile index past the
-  // last one re-sends the last tile (into a slot nobody reads), rows past the end of the cache
-  // repeat the last valid row, so every step issues the same number of loads
-  auto dma_piece = [&](const __bf16* head_base, const unsigned (&cc)[LOADS], int kt, u32x4* dst, int i)
-      __attribute__((always_inline)) {
-    const int kte = min(kt, nt - 1);
-    const __bf16* base = head_base + static_cast<long long>(kte) * BN * row_stride;
-    const int lim = total - 1 - kte * BN;
-    const unsigned o32 = 2u * (static_cast<unsigned>(min(ld_row[i], lim)) * row_stride + cc[i]);
-    const unsigned lds_addr = static_cast<unsigned>(reinterpret_cast<uintptr_t>(
-        (lds_void*)(dst + (i * kWaves + wave) * 64)));
-    lds_dma16(base, o32, lds_addr);
+  // tile kt of K (or V) -> ring slot buf; rows past the end of the cache repeat the last valid row
+  auto dma_tile = [&](const __bf16* head_base, const unsigned (&off)[LOADS], const unsigned (&cc)[LOADS],
+                      int kt, u32x4* dst) {
+    const __bf16* base = head_base + static_cast<long long>(kt) * BN * row_stride;
+    const int lim = total - 1 - kt * BN;
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+      const unsigned o32 = (lim >= BN - 1) ? off[i]
+                                           : 2u * (static_cast<unsigned>(min(ld_row[i], lim)) * row_stride + cc[i]);
+      const unsigned lds_addr = static_cast<unsigned>(reinterpret_cast<uintptr_t>(
+          (lds_void*)(dst + (i * kWaves + wave) * 64)));
+      lds_dma16(base, o32, lds_addr);
+    }
   };
-  // staging step s moves K tile s+1 and V tile s: 2 * LOADS loads, numbered 0 .. 2 LOADS - 1
-  auto stage_piece = [&](int s, int which) __attribute__((always_inline)) {
-    if (which < LOADS) dma_piece(kbase, ld_kcc, s + 1, ldsK((s + 1) % kStages), which);
-    else dma_piece(vbase, ld_vcc, s, ldsV(s % kStages), which - LOADS);
+  // staging step s moves K tile s+1 and V tile s; returns the number of loads it issued
+  auto stage = [&](int s) -> int {
+    int cnt = 0;
+    if (s + 1 < nt) { dma_tile(kbase, koff, ld_kcc, s + 1, ldsK((s + 1) % kStages)); cnt += LOADS; }
+    if (s < nt) { dma_tile(vbase, voff, ld_vcc, s, ldsV(s % kStages)); cnt += LOADS; }
+    return cnt;
   };
 
   f32x16 o[DB];
@@ -199,10 +201,9 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_attn_kernel(AttnArgs a) {
   // ---- prologue: K tiles 0..2 and V tiles 0..1 on their way into LDS -----------------------------
   // the first MFMA block multiplies a zero P by the ring slot "before" V tile 0: make it finite
   for (int i = tid; i < TILE; i += kThreads) ldsV(kStages - 1)[i] = u32x4{0u, 0u, 0u, 0u};
-#pragma unroll
-  for (int i = 0; i < LOADS; ++i) dma_piece(kbase, ld_kcc, 0, ldsK(0), i);
-#pragma unroll
-  for (int w = 0; w < 2 * LOADS; ++w) stage_piece(0, w);
+  dma_tile(kbase, koff, ld_kcc, 0, ldsK(0));
+  stage(0);
+  stage(1);
   // every load so far (the Q fragment included) is drained here: a load left pending across the
   // loop entry would make the compiler guard the loop's MFMAs with vmcnt waits
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
@@ -210,165 +211,132 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_attn_kernel(AttnArgs a) {
   if (phase == 1) __syncthreads();   // second group runs one barrier behind the first
 
   f32x16 s[2];
-  u32x4 pf[2][2];   // P as packed bf16 pairs: B operand of the P.V MFMAs
+  bf16x8 pf[2][2];
 #pragma unroll
   for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-    for (int si = 0; si < 2; ++si) pf[mb][si] = u32x4{0u, 0u, 0u, 0u};
+    for (int si = 0; si < 2; ++si)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) pf[mb][si][e] = static_cast<__bf16>(0.0f);
 
-  // ---- softmax of tile jj: S (in s[]) -> P (in pf[]), running m / l / O re-based when needed --
-  auto softmax_tile = [&](const int jj) __attribute__((always_inline)) {
-    // register e of block mb is key  jj*BN + 32 mb + 8 (e/4) + 4 kg + e%4  of query n
-    if (jj * BN + BN - 1 > wmin) {
-      int rel = qpos - jj * BN - 4 * kg;   // largest still-visible key offset (minus 4 kg)
-      // opaque to the optimiser: otherwise the 32 compares below become 32 loop-carried
-      // counters that are kept up to date (and kept in registers) on every tile
-      asm volatile("" : "+v"(rel));
+  // One tile step; RS = j % kStages is a compile-time value so that every LDS operand address is
+  // a loop-invariant per-lane register plus an immediate.
+  auto tile_step = [&](const int j, auto rs_tag) {
+    constexpr int RS = decltype(rs_tag)::value;
+    // ================= MFMA block =================
+    // P.V of tile j-1 followed by K.Q^T of tile j as ONE software-pipelined stream of operand reads
+    // and MFMAs: the LDS read of op i + PF is issued before the MFMA of op i, and the compiler is
+    // told not to move anything across the steps.  The block runs whole for j <= jw: at j = 0 the
+    // P fragment is zero and the "previous" V slot was zero-filled, at j = jw the scores it forms
+    // are never looked at (the price is one tile's worth of MFMAs per wave, the gain is a single
+    // straight-line block).
+    if (j <= jw) {
+      const short* Vb = reinterpret_cast<const short*>(ldsV((RS + kStages - 1) % kStages));
+      const bf16x8* Kb = reinterpret_cast<const bf16x8*>(ldsK(RS));
+      // contraction slot 4e + t of P.V step (mb, si) is key 32 mb + 16 si + 8 e + 4 kg + t on both operands
+      auto vread = [&](int idx) -> bf16x8 {
+        const int mb = idx / (2 * DB), si = (idx / DB) % 2, db = idx % DB;
+        s16x8 vf;
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          const int row = 32 * mb + 16 * si + 8 * e + v_row0;
+          const int slot = (4 * db + v_cc0) ^ v_sw;
+          const short* p = Vb + (row * CPR + slot) * 8 + v_sub;
+          const s16x4 t = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
+          vf[4 * e + 0] = t[0]; vf[4 * e + 1] = t[1]; vf[4 * e + 2] = t[2]; vf[4 * e + 3] = t[3];
+        }
+        return __builtin_bit_cast(bf16x8, vf);
+      };
+      auto kread = [&](int idx) -> bf16x8 {
+        const int ks = idx / 2, mb = idx % 2;
+        return Kb[(32 * mb + n) * CPR + ((2 * ks + kg) ^ k_sw)];
+      };
+      constexpr int N0 = 4 * DB, N = N0 + 2 * KS;
+      auto frag = [&](int i) -> bf16x8 { return (i < N0) ? vread(i) : kread(i - N0); };
+      bf16x8 fq[PF];
+#pragma unroll
+      for (int i = 0; i < PF; ++i) fq[i] = frag(i);
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-        for (int e = 0; e < 16; ++e)
-          if (32 * mb + 8 * (e / 4) + (e % 4) > rel) s[mb][e] = -INFINITY;
-    }
-    // online softmax in base 2 with a lazily moved exponent reference
-    float tmax = s[0][0];
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) tmax = fmaxf(tmax, s[mb][e]);
-    tmax = fmaxf(tmax, other_half(tmax)) * c;
-    // p = exp2(s c - m) stays <= 2^slack as long as the tile max is within the slack of m;
-    // only when some row of the wave outgrows it are m, l and O re-based (wave-uniform branch)
-    if (__builtin_amdgcn_ballot_w64(tmax > m + kRescaleSlack) != 0) {
-      const float mnew = fmaxf(m, tmax);
-      const float alpha = __builtin_amdgcn_exp2f(m - mnew);
-      l *= alpha;
-      m = mnew;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) o[db][e] *= alpha;
-    }
-    // P is rounded to bf16 in pairs; the row sum adds up the rounded values (v_dot2c with ones),
-    // i.e. exactly the weights the P.V product uses
-    const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-      for (int e = 0; e < 16; e += 2) {
-        const float p0 = __builtin_amdgcn_exp2f(fmaf(s[mb][e], c, -m));
-        const float p1 = __builtin_amdgcn_exp2f(fmaf(s[mb][e + 1], c, -m));
-        const bf16x2 pp = {static_cast<__bf16>(p0), static_cast<__bf16>(p1)};
-        l = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, l, false);
-        pf[mb][e / 8][(e % 8) / 2] = __builtin_bit_cast(unsigned, pp);
-      }
-  };
-
-  // ---- K/V tiles for two steps ahead leave for LDS; then wait for those sent one step ago ---------
-  auto send_tiles = [&](const int j) __attribute__((always_inline)) {
-#pragma unroll
-    for (int w = 0; w < 2 * LOADS; ++w) stage_piece(j + 1, w);
-  };
-  auto await_tiles = [&]() __attribute__((always_inline)) {
-    // the loads issued one step ago (tiles K(j+1), V(j)) have landed once at most this step's
-    // 2 LOADS are still in flight
-    __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * LOADS));
-  };
-
-  // ---- MFMA block of step j: P.V of tile j-1, then K.Q^T of tile j -------------------------------
-  // ONE software-pipelined stream of operand reads and MFMAs: the LDS read of op i + PF is issued
-  // before the MFMA of op i, and the compiler is told not to move anything across the steps.  At
-  // j = 0 the P fragment is zero and the "previous" V slot was zero-filled; in a wave's last step
-  // the scores it forms are never looked at (the price is one tile's worth of MFMAs per wave, the
-  // gain is a single straight-line block).  RS = j % kStages is a compile-time value so that every
-  // LDS operand address is a loop-invariant per-lane register plus an immediate.
-  auto mfma_block = [&](const int j, auto rs_tag) __attribute__((always_inline)) {
-    constexpr int RS = decltype(rs_tag)::value;
-    const short* Vb = reinterpret_cast<const short*>(ldsV((RS + kStages - 1) % kStages));
-    const bf16x8* Kb = reinterpret_cast<const bf16x8*>(ldsK(RS));
-    // contraction slot 4e + t of P.V step (mb, si) is key 32 mb + 16 si + 8 e + 4 kg + t on both operands
-    auto vread = [&](int idx) -> bf16x8 {
-      const int mb = idx / (2 * DB), si = (idx / DB) % 2, db = idx % DB;
-      s16x8 vf;
-#pragma unroll
-      for (int e = 0; e < 2; ++e) {
-        const int row = 32 * mb + 16 * si + 8 * e + v_row0;
-        const int slot = (4 * db + v_cc0) ^ v_sw;
-        const short* p = Vb + (row * CPR + slot) * 8 + v_sub;
-        const s16x4 t = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
-        vf[4 * e + 0] = t[0]; vf[4 * e + 1] = t[1]; vf[4 * e + 2] = t[2]; vf[4 * e + 3] = t[3];
-      }
-      return __builtin_bit_cast(bf16x8, vf);
-    };
-    auto kread = [&](int idx) -> bf16x8 {
-      const int ks = idx / 2, mb = idx % 2;
-      return Kb[(32 * mb + n) * CPR + ((2 * ks + kg) ^ k_sw)];
-    };
-    constexpr int N0 = 4 * DB, N = N0 + 2 * KS;
-    constexpr int DMA_EVERY = (N - 4) / (2 * LOADS);
-    auto frag = [&](int i) -> bf16x8 { return (i < N0) ? vread(i) : kread(i - N0); };
-    const f32x16 zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f,
-                         0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
-    bf16x8 fq[PF];
-#pragma unroll
-    for (int i = 0; i < PF; ++i) fq[i] = frag(i);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int i = 0; i < N; ++i) {
-      const bf16x8 cur = fq[i % PF];
-      if (i + PF < N) fq[i % PF] = frag(i + PF);
-      // the K/V tiles for two steps ahead leave for LDS in the shadow of the MFMAs
-      if (i >= 2 && (i - 2) % DMA_EVERY == 0 && (i - 2) / DMA_EVERY < 2 * LOADS) stage_piece(j + 1, (i - 2) / DMA_EVERY);
-      if (i < N0) {
-        const int mb = i / (2 * DB), si = (i / DB) % 2, db = i % DB;
-        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, __builtin_bit_cast(bf16x8, pf[mb][si]), o[db], 0, 0, 0);
-      } else {
-        const int q = i - N0;
-        s[q % 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, qf[q / 2], (q < 2) ? zero : s[q % 2], 0, 0, 0);
-      }
+        for (int e = 0; e < 16; ++e) s[mb][e] = 0.0f;
       __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < N; ++i) {
+        const bf16x8 cur = fq[i % PF];
+        if (i + PF < N) fq[i % PF] = frag(i + PF);
+        if (i < N0) {
+          const int mb = i / (2 * DB), si = (i / DB) % 2, db = i % DB;
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, pf[mb][si], o[db], 0, 0, 0);
+        } else {
+          const int q = i - N0;
+          s[q % 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, qf[q / 2], s[q % 2], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
-  };
+    __syncthreads();
 
-  // ---- the steps of one wave -----------------------------------------------------------------------
-  // full step j < jw:  [MFMA block (sends tiles on the way), await] barrier [softmax of tile j] barrier
-  // last step j = jw:  [MFMA block (its P.V half is what counts), await] barrier, barrier
-  // idle steps j > jw (waves whose rows end above the workgroup's last key tile): staging only
-  auto full_step = [&](const int j, auto rs_tag) __attribute__((always_inline)) {
-    mfma_block(j, rs_tag);
-    await_tiles();
-    __syncthreads();
-    softmax_tile(j);
+    // ================= VALU block =================
+    // staging: this wave's step is j + phase (the late group is one tile ahead in tile numbers);
+    // tiles K(st+2), V(st+1) start their trip now and are awaited one period later
+    const int st = j + phase;
+    const int issued = (st >= 1) ? stage(st + 1) : 0;
+    if (j < jw) {
+      // register e of block mb is key  j*BN + 32 mb + 8 (e/4) + 4 kg + e%4  of query n
+      if (j * BN + BN - 1 > wmin) {
+        int rel = qpos - j * BN - 4 * kg;   // largest still-visible key offset (minus 4 kg)
+        // opaque to the optimiser: otherwise the 32 compares below become 32 loop-carried
+        // counters that are kept up to date (and kept in registers) on every tile
+        asm volatile("" : "+v"(rel));
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+          for (int e = 0; e < 16; ++e)
+            if (32 * mb + 8 * (e / 4) + (e % 4) > rel) s[mb][e] = -INFINITY;
+      }
+      // ---- online softmax (base 2) with a lazily moved exponent reference -------------------
+      float tmax = s[0][0];
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) tmax = fmaxf(tmax, s[mb][e]);
+      tmax = fmaxf(tmax, other_half(tmax)) * c;
+      // p = exp2(s c - m) stays <= 2^slack as long as the tile max is within the slack of m;
+      // only when some row of the wave outgrows it are m, l and O re-based (wave-uniform branch)
+      if (__builtin_amdgcn_ballot_w64(tmax > m + kRescaleSlack) != 0) {
+        const float mnew = fmaxf(m, tmax);
+        const float alpha = __builtin_amdgcn_exp2f(m - mnew);
+        l *= alpha;
+        m = mnew;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) o[db][e] *= alpha;
+      }
+      float psum = 0.0f;
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const float p = __builtin_amdgcn_exp2f(fmaf(s[mb][e], c, -m));
+          psum += p;
+          pf[mb][e / 8][e % 8] = static_cast<__bf16>(p);
+        }
+      l += psum;
+    }
+    // everything issued before this block (tiles K(st+1), V(st)) must have landed before the barrier
+    if (issued == 2 * LOADS) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * LOADS));
+    else if (issued == LOADS) __builtin_amdgcn_s_waitcnt(0x0F70 | LOADS);
+    else __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
   };
-  {
-    int j = 0;
-    while (j < jw) {
-      full_step(j, std::integral_constant<int, 0>{});
-      if (++j >= jw) break;
-      full_step(j, std::integral_constant<int, 1>{});
-      if (++j >= jw) break;
-      full_step(j, std::integral_constant<int, 2>{});
-      ++j;
-    }
-    static_assert(kStages == 3, "the unrolled loop above is written for a ring of three");
-    if (jw > 0) {   // j == jw
-      const int rs = j % kStages;
-      if (rs == 0) mfma_block(j, std::integral_constant<int, 0>{});
-      else if (rs == 1) mfma_block(j, std::integral_constant<int, 1>{});
-      else mfma_block(j, std::integral_constant<int, 2>{});
-      await_tiles();
-      __syncthreads();
-      __syncthreads();
-      ++j;
-    }
-    for (; j <= nt; ++j) {
-      send_tiles(j);
-      await_tiles();
-      __syncthreads();
-      __syncthreads();
-    }
+  for (int j0 = 0; j0 <= nt; j0 += kStages) {
+    tile_step(j0, std::integral_constant<int, 0>{});
+    if (j0 + 1 <= nt) tile_step(j0 + 1, std::integral_constant<int, 1>{});
+    if (j0 + 2 <= nt) tile_step(j0 + 2, std::integral_constant<int, 2>{});
   }
+  static_assert(kStages == 3, "the unrolled loop above is written for a ring of three");
   if (phase == 0) __syncthreads();   // both groups execute the same number of barriers
 
   // ---- epilogue: O / l, bf16, store -----------------------------------------------------------
