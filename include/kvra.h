@@ -15,9 +15,8 @@
  *   - Return value: KVRA_OK, or a negative code; on error nothing was enqueued.
  *   - head_dim must be 64 or 128; n_q_heads must be a multiple of n_kv_heads; query head h
  *     reads key/value head h / (n_q_heads / n_kv_heads).
- *   - kvra_chunk_attn keeps partial results in a per-device workspace that the library allocates
- *     on first use and grows on demand (hipMalloc, cached until the process ends); calls that
- *     overlap on one device from different streams must not share it and are not supported.
+ *   - No entry point allocates device memory or keeps state between calls: every intermediate
+ *     of kvra_chunk_attn lives in registers and LDS, so calls on different streams may overlap.
  */
 #ifndef KVRA_H
 #define KVRA_H
@@ -33,7 +32,7 @@ enum {
   KVRA_EINVAL = -1,       /* null pointer, non-positive size, heads not divisible, bad scale   */
   KVRA_EUNSUPPORTED = -2, /* head_dim other than 64 / 128, or a size beyond the 32-bit tiling   */
   KVRA_ERANGE = -3,       /* prefix_len + chunk_len exceeds the cache capacity                  */
-  KVRA_ELAUNCH = -4,      /* the HIP runtime refused the launch or an allocation                */
+  KVRA_ELAUNCH = -4,      /* the HIP runtime refused the launch                                  */
   KVRA_ENODEVICE = -5     /* no usable gfx950 device                                            */
 };
 
