@@ -71,6 +71,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the equal-split comparison runs")
+    ap.add_argument("--workload", default=WORKLOAD,
+                    help="a key of synth.CONFIGS; the default is the workload the metric is quoted on")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also issue one plain 256 MiB device-to-device copy (outside the timed region) so "
                          "that a rocprofv3 --pmc run holds a dispatch of known traffic to scale counters by")
@@ -87,7 +89,7 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
-    cfg = synth.CONFIGS[WORKLOAD]
+    cfg = synth.CONFIGS[args.workload]
     C, H, Hkv, d = cfg["C"], cfg["H"], cfg["Hkv"], cfg["d"]
     bounds = cfg["boundaries"]
     p = len(bounds) - 1
@@ -164,11 +166,11 @@ def main():
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": WORKLOAD, "context_len": C, "n_q_heads": H, "n_kv_heads": Hkv, "head_dim": d,
+        "config": {"workload": args.workload, "context_len": C, "n_q_heads": H, "n_kv_heads": Hkv, "head_dim": d,
                    "chunks": p, "boundaries": bounds, "useful_gflop_per_step": flops_step / 1e9},
         "pct_of_bf16_peak": 100.0 * flops_step / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "roofline": {"kernel": "chunk_attn_kernel", "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": ATTN_TRAFFIC_BYTES,
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": ATTN_TRAFFIC_BYTES if args.workload == WORKLOAD else None,
                      "avg_launch_ms": attn_avg_launch_ms},
         "per_chunk": {"attn_ms": [round(float(x), 4) for x in attn_mean],
                       "append_ms": [round(float(x), 4) for x in append_mean],

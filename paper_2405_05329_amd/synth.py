@@ -21,6 +21,12 @@ CONFIGS = {
                                  boundaries=[0, 4096, 5824, 7104, 8192]),
     "llama7b_32k_balanced": dict(cfg_id=5, H=32, Hkv=32, d=128, C=32768,
                                  boundaries=[0, 11584, 16384, 20096, 23168, 25920, 28352, 30656, 32768]),
+    # grouped-query and multi-query variants of the Llama-7B shape (Sec. 5, the GQA8 / MQA rows of the
+    # model table), on the 16k balanced boundaries
+    "llama7b_gqa8_16k_balanced": dict(cfg_id=6, H=32, Hkv=8, d=128, C=16384,
+                                      boundaries=[0, 5824, 8192, 10048, 11584, 12928, 14208, 15296, 16384]),
+    "llama7b_mqa_16k_balanced": dict(cfg_id=7, H=32, Hkv=1, d=128, C=16384,
+                                     boundaries=[0, 5824, 8192, 10048, 11584, 12928, 14208, 15296, 16384]),
 }
 ROPE_BASE = 10000.0
 

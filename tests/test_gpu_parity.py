@@ -201,7 +201,9 @@ def _sample_rows(boundaries, n_random, seed):
     return sorted(r for r in rows if 0 <= r < C)
 
 
-@pytest.mark.parametrize("name,n_random", [("llama7b_16k_balanced", 48), ("falcon7b_8k_balanced", 64)])
+@pytest.mark.parametrize("name,n_random", [("llama7b_16k_balanced", 48), ("falcon7b_8k_balanced", 64),
+                                           ("llama7b_32k_balanced", 32), ("llama7b_gqa8_16k_balanced", 32),
+                                           ("llama7b_mqa_16k_balanced", 32)])
 def test_paper_shapes_sampled_rows(name, n_random):
     cfg = synth.CONFIGS[name]
     q, k, v, scale, res = _run(cfg["cfg_id"], 0, cfg["C"], cfg["H"], cfg["Hkv"], cfg["d"], cfg["boundaries"])
