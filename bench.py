@@ -245,6 +245,42 @@ def main():
                 tot += np.array([x[0].elapsed_time(x[2]) for x in e])
         result["makespan"]["kvra_balance_measured_ms"] = float((tot / reps).max())
 
+        def measured_makespan(bnds):
+            acc = np.zeros(len(bnds) - 1)
+            for rep in range(reps + 1):
+                qw3 = q_work[rep % n_buf]
+                qw3.copy_(q_master)
+                e = new_events(len(bnds) - 1)
+                run_step(bnds, qw3, e)
+                torch.cuda.synchronize()
+                if rep:
+                    acc += np.array([x[0].elapsed_time(x[2]) for x in e])
+            return float((acc / reps).max())
+
+        # the paper's own search (hierarchical grid search, KVR-S) on the same fitted cost, from the
+        # even split as in the paper and seeded with the exact optimum of the analytic model
+        gs_b, gs_m, gs_ev = kvra.kvra_search_grid(C, p, 64, cost)
+        seed_b, _ = kvra.kvra_balance(C, p, 64)
+        gs2_b, gs2_m, gs2_ev = kvra.kvra_search_grid(C, p, 64, cost, start=seed_b)
+        result["makespan"]["grid_search"] = {
+            "from_even_split": {"boundaries": gs_b, "predicted_ms": gs_m, "cost_evaluations": gs_ev,
+                                "measured_ms": measured_makespan(gs_b)},
+            "seeded": {"boundaries": gs2_b, "predicted_ms": gs2_m, "cost_evaluations": gs2_ev,
+                       "measured_ms": measured_makespan(gs2_b)}}
+        # lookup table at 4k spacing and predicted partitionings (KVR-P) for lengths between entries,
+        # against the partitioning searched at that length (KVR-S) and the even split (KVR-E)
+        if C >= 16384:
+            lut = {L: kvra.kvra_balance(L, p, 64, cost)[0] for L in (4096, 8192, 12288, 16384)}
+            pred = {}
+            for L in (10240, 14336):
+                kvr_p = kvra.kvra_table_predict(L, 64, lut)
+                kvr_s = kvra.kvra_balance(L, p, 64, cost)[0]
+                kvr_e = kvra.kvra_equal_split(L, p, 64)
+                pred[str(L)] = {"kvr_p_boundaries": kvr_p, "kvr_p_ms": measured_makespan(kvr_p),
+                                "kvr_s_boundaries": kvr_s, "kvr_s_ms": measured_makespan(kvr_s),
+                                "kvr_e_ms": measured_makespan(kvr_e)}
+            result["makespan"]["lookup_table_4k_spacing"] = pred
+
     if not args.no_cpu_baseline:
         del q_work
         torch.cuda.empty_cache()

@@ -115,6 +115,62 @@ int kvra_equal_split(int64_t context_len, int n_chunks, int64_t granularity, int
 int kvra_makespan(const int64_t* boundaries, int n_chunks, kvra_cost_fn cost, void* user,
                   double* makespan_out);
 
+/*
+ * One-dimensional search for two processes (Sec. 4.2, the two-partition panel of the search
+ * figure): the first process's cost grows and the second's shrinks as the interior boundary moves
+ * right, so the crossing is found by bisection in O(log(context_len/granularity)) cost
+ * evaluations and the better of the two grid points around it is returned (ties: the smaller
+ * boundary).  Exact when cost(0, c) is non-decreasing and cost(b, C - b) non-increasing in the
+ * boundary; otherwise still a valid partition.
+ *   boundaries_out   host array of 3 entries;  makespan_out, evaluations_out   host scalars or NULL
+ * Errors (KVRA_EINVAL): as kvra_balance with n_chunks = 2.
+ */
+int kvra_search_two_way(int64_t context_len, int64_t granularity, kvra_cost_fn cost, void* user,
+                        int64_t* boundaries_out, double* makespan_out, int64_t* evaluations_out);
+
+/*
+ * Hierarchical grid search (Sec. 4.2, search figure panels with strides 8/4/2; appendix on lookup
+ * table generation: five values per boundary and level).  Level by level every interior boundary
+ * is tried at its current value + {-2,-1,0,1,2} * stride; of all 5^(n_chunks-1) combinations that
+ * are strictly rising inside (0, context_len) the one with the smallest makespan (ties: the
+ * lexicographically smallest) becomes the centre of the next level, whose stride is half as
+ * large.  The first stride is the largest granularity * 2^k with 2 * stride < context_len /
+ * n_chunks; the last is `granularity`.  A heuristic: its reach is limited to about two first
+ * strides around the starting point.
+ *   start            host array of n_chunks + 1 entries (a valid partition on the grid), or NULL for
+ *                    the even split
+ *   boundaries_out   host array of n_chunks + 1 entries (never worse than `start`)
+ *   makespan_out, evaluations_out (number of cost callbacks made)   host scalars or NULL
+ * Errors (KVRA_EINVAL): as kvra_balance; `start` not a partition of context_len on the grid.
+ */
+int kvra_search_grid(int64_t context_len, int n_chunks, int64_t granularity, const int64_t* start,
+                     kvra_cost_fn cost, void* user, int64_t* boundaries_out, double* makespan_out,
+                     int64_t* evaluations_out);
+
+/*
+ * Predicted partitioning from two lookup-table entries (KVR-P; Sec. 4.2, and the partitioning
+ * paragraph of Sec. 5 that interpolates 8k and 12k entries for a 10k context).  The cumulative
+ * ratios b_k / length of the two entries are blended linearly in context_len (clamped to the
+ * nearer entry outside [len_lo, len_hi]), scaled by context_len and rounded to the nearest
+ * multiple of `granularity` (halves up); colliding boundaries are pushed one granule apart.
+ *   bounds_lo, bounds_hi   host arrays of n_chunks + 1 strictly rising entries, 0 .. len_lo / len_hi
+ *   boundaries_out         host array of n_chunks + 1 entries
+ * Errors (KVRA_EINVAL): bad grid, len_hi < len_lo, entries that are not partitions of their length.
+ */
+int kvra_interpolate(int64_t context_len, int n_chunks, int64_t granularity,
+                     int64_t len_lo, const int64_t* bounds_lo,
+                     int64_t len_hi, const int64_t* bounds_hi, int64_t* boundaries_out);
+
+/*
+ * Prediction from a whole lookup table (the partitioning table of the overview figure): picks the
+ * two entries that bracket context_len (the nearest single entry outside the table's range) and
+ * applies kvra_interpolate.
+ *   entry_lens     host array [n_entries], any order
+ *   entry_bounds   host array [n_entries][n_chunks + 1], row e partitions entry_lens[e]
+ */
+int kvra_table_predict(int64_t context_len, int n_chunks, int64_t granularity, int n_entries,
+                       const int64_t* entry_lens, const int64_t* entry_bounds, int64_t* boundaries_out);
+
 #ifdef __cplusplus
 }
 #endif

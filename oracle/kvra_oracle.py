@@ -324,3 +324,109 @@ def brute_force_balance(context_len, p, granularity, cost=analytic_cost):
         if best is None or m < best:
             best, best_b = m, b
     return best_b, best
+
+
+# --------------------------------------------------------------------------- partition search
+# Sec. 4.2 describes three off-line tools on top of the makespan objective: a one-dimensional
+# search for two processes, a hierarchical grid search for more, and a lookup table whose
+# entries are linearly interpolated at inference time.  The paper drives them with measured
+# TTFT; here the objective is the makespan of per-chunk costs.  Details the paper leaves open
+# (stride schedule, what "zooming in" keeps, rounding of interpolated boundaries) are fixed
+# as stated in each docstring.
+def two_way_scan(context_len, granularity, cost=analytic_cost):
+    """Best split of a context between two processes by trying every grid position of the
+    single interior boundary (what the paper's one-dimensional search converges to,
+    Sec. 4.2 / Fig. 6(a)).  Ties go to the smaller boundary.  Returns (boundaries, makespan)."""
+    g = granularity
+    best, best_b = None, None
+    for b1 in range(g, context_len, g):
+        m = makespan([0, b1, context_len], cost)
+        if best is None or m < best:
+            best, best_b = m, [0, b1, context_len]
+    return best_b, best
+
+
+def grid_search_strides(context_len, p, granularity):
+    """Stride schedule of the hierarchical grid search: the first stride is the largest
+    granularity * 2^k with 2 * stride < C / p, then it halves down to the granularity.
+    For the paper's example (C = 96, granularity 2, three or four partitions) this gives
+    8, 4, 2 as in Fig. 6(b-d)."""
+    stride = granularity
+    while 2 * (2 * stride) * p < context_len:
+        stride *= 2
+    out = []
+    while stride >= granularity:
+        out.append(stride)
+        stride //= 2
+    return out
+
+
+def hierarchical_grid_search(context_len, p, granularity, cost=analytic_cost, start=None):
+    """Hierarchical grid search of Sec. 4.2 (Fig. 6(b-d); cost model in the appendix on lookup
+    table generation: five values per interior boundary and level).
+
+    Level by level, every interior boundary is tried at its current value plus
+    {-2,-1,0,1,2} * stride, all 5^(p-1) combinations; combinations that are not strictly
+    rising inside (0, C) are dropped; the combination with the smallest makespan (ties: the
+    lexicographically smallest boundary vector) becomes the centre of the next level, whose
+    stride is half as large, so the next level scans exactly +-1 old stride around it.
+    Starts from the even split unless `start` is given.  Returns (boundaries, makespan, levels)
+    where levels is the list of (stride, centre after the level).
+    """
+    cur = list(start) if start is not None else equal_split(context_len, p, granularity)
+    assert cur[0] == 0 and cur[-1] == context_len and len(cur) == p + 1
+    levels = []
+    best_m = makespan(cur, cost)
+    for stride in grid_search_strides(context_len, p, granularity):
+        axes = [[cur[k] + o * stride for o in (-2, -1, 0, 1, 2)] for k in range(1, p)]
+        best, best_b = None, None
+        for inner in itertools.product(*axes):
+            b = [0] + list(inner) + [context_len]
+            if any(b[i + 1] <= b[i] for i in range(p)):
+                continue
+            m = makespan(b, cost)
+            if best is None or m < best or (m == best and b < best_b):
+                best, best_b = m, b
+        cur, best_m = best_b, best
+        levels.append((stride, list(cur)))
+    return cur, best_m, levels
+
+
+def interpolate_partition(context_len, granularity, len_lo, bounds_lo, len_hi, bounds_hi):
+    """Predicted partitioning of a context from two lookup-table entries (KVR-P, Sec. 4.2 and
+    the partitioning paragraph of Sec. 5): the cumulative boundary RATIOS b_k / C of the two
+    entries are blended linearly in the context length, scaled by the new length and rounded
+    to the nearest grid point (halves up).  A length outside [len_lo, len_hi] takes the ratios
+    of the nearer entry.  Boundaries that collide after rounding are pushed apart by one
+    granule, first upwards from the left, then downwards from the right.
+    """
+    p = len(bounds_lo) - 1
+    assert len(bounds_hi) == p + 1
+    g = granularity
+    if len_hi == len_lo:
+        w = 0.0
+    else:
+        w = (context_len - len_lo) / (len_hi - len_lo)
+        w = min(1.0, max(0.0, w))
+    b = [0] * (p + 1)
+    for k in range(1, p):
+        r = (1.0 - w) * (bounds_lo[k] / len_lo) + w * (bounds_hi[k] / len_hi)
+        b[k] = g * int(math.floor(r * context_len / g + 0.5))
+    b[p] = context_len
+    for k in range(1, p):
+        if b[k] < b[k - 1] + g:
+            b[k] = b[k - 1] + g
+    for k in range(p - 1, 0, -1):
+        if b[k] > b[k + 1] - g:
+            b[k] = b[k + 1] - g
+    return b
+
+
+def lookup_partition(context_len, granularity, table):
+    """Prediction from a lookup table {context length: boundaries} (Fig. 3(b)): blend the two
+    entries that bracket the length; below the smallest or above the largest entry the
+    nearest entry's ratios are used."""
+    lens = sorted(table)
+    lo = max([x for x in lens if x <= context_len], default=lens[0])
+    hi = min([x for x in lens if x >= context_len], default=lens[-1])
+    return interpolate_partition(context_len, granularity, lo, table[lo], hi, table[hi])

@@ -54,6 +54,15 @@ def _load() -> ctypes.CDLL:
     lib.kvra_equal_split.argtypes = [i64, i32, i64, ctypes.POINTER(i64)]
     lib.kvra_makespan.restype = i32
     lib.kvra_makespan.argtypes = [ctypes.POINTER(i64), i32, ctypes.c_void_p, vp, ctypes.POINTER(ctypes.c_double)]
+    pi64, pf64 = ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)
+    lib.kvra_search_two_way.restype = i32
+    lib.kvra_search_two_way.argtypes = [i64, i64, ctypes.c_void_p, vp, pi64, pf64, pi64]
+    lib.kvra_search_grid.restype = i32
+    lib.kvra_search_grid.argtypes = [i64, i32, i64, pi64, ctypes.c_void_p, vp, pi64, pf64, pi64]
+    lib.kvra_interpolate.restype = i32
+    lib.kvra_interpolate.argtypes = [i64, i32, i64, i64, pi64, i64, pi64, pi64]
+    lib.kvra_table_predict.restype = i32
+    lib.kvra_table_predict.argtypes = [i64, i32, i64, i32, pi64, pi64, pi64]
     return lib
 
 
@@ -148,3 +157,70 @@ def kvra_makespan(boundaries, cost=None) -> float:
     if rc != KVRA_OK:
         raise KvraError(rc, "kvra_makespan")
     return mk.value
+
+
+def _i64_array(values):
+    v = [int(x) for x in values]
+    return (ctypes.c_int64 * len(v))(*v)
+
+
+def kvra_search_two_way(context_len, granularity, cost=None):
+    """Returns (boundaries list of 3, makespan, cost evaluations)."""
+    out = (ctypes.c_int64 * 3)()
+    mk, ev = ctypes.c_double(), ctypes.c_int64()
+    cb, cbp = _cost(cost)
+    rc = _lib.kvra_search_two_way(int(context_len), int(granularity), cbp, None, out, ctypes.byref(mk),
+                                  ctypes.byref(ev))
+    if rc != KVRA_OK:
+        raise KvraError(rc, "kvra_search_two_way")
+    return list(out), mk.value, ev.value
+
+
+def kvra_search_grid(context_len, n_chunks, granularity, cost=None, start=None):
+    """Returns (boundaries list, makespan, cost evaluations).  start: a partition on the grid, or None
+    for the even split."""
+    n = int(n_chunks)
+    out = (ctypes.c_int64 * (max(n, 0) + 1))()
+    mk, ev = ctypes.c_double(), ctypes.c_int64()
+    cb, cbp = _cost(cost)
+    st = None
+    if start is not None:
+        if len(start) != n + 1:
+            raise KvraError(KVRA_EINVAL, "kvra_search_grid")
+        st = _i64_array(start)
+    rc = _lib.kvra_search_grid(int(context_len), n, int(granularity), st, cbp, None, out, ctypes.byref(mk),
+                               ctypes.byref(ev))
+    if rc != KVRA_OK:
+        raise KvraError(rc, "kvra_search_grid")
+    return list(out), mk.value, ev.value
+
+
+def kvra_interpolate(context_len, granularity, len_lo, bounds_lo, len_hi, bounds_hi):
+    n = len(bounds_lo) - 1
+    if n < 1 or len(bounds_hi) != n + 1:
+        raise KvraError(KVRA_EINVAL, "kvra_interpolate")
+    out = (ctypes.c_int64 * (n + 1))()
+    rc = _lib.kvra_interpolate(int(context_len), n, int(granularity), int(len_lo), _i64_array(bounds_lo),
+                               int(len_hi), _i64_array(bounds_hi), out)
+    if rc != KVRA_OK:
+        raise KvraError(rc, "kvra_interpolate")
+    return list(out)
+
+
+def kvra_table_predict(context_len, granularity, table):
+    """table: {context length: boundaries}; all entries with the same number of chunks."""
+    lens = list(table)
+    if not lens:
+        raise KvraError(KVRA_EINVAL, "kvra_table_predict")
+    n = len(table[lens[0]]) - 1
+    flat = []
+    for length in lens:
+        if len(table[length]) != n + 1:
+            raise KvraError(KVRA_EINVAL, "kvra_table_predict")
+        flat.extend(table[length])
+    out = (ctypes.c_int64 * (n + 1))()
+    rc = _lib.kvra_table_predict(int(context_len), n, int(granularity), len(lens), _i64_array(lens),
+                                 _i64_array(flat), out)
+    if rc != KVRA_OK:
+        raise KvraError(rc, "kvra_table_predict")
+    return list(out)

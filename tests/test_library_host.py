@@ -145,3 +145,85 @@ def test_balance_closed_form_and_bounds():
 def test_equal_split_matches_oracle_rounding():
     for C, p, g in [(256, 3, 64), (4096, 4, 64), (960, 7, 64), (100, 3, 1)]:
         assert kvra.kvra_equal_split(C, p, g) == orc.equal_split(C, p, g)
+
+
+# ---------------------------------------------------------------- partition search tools (Sec. 4.2)
+def _table_cost(seed):
+    rnd = random.Random(seed)
+    table = {}
+    def cost(prefix, c):
+        if (prefix, c) not in table:
+            table[(prefix, c)] = rnd.choice([1.0, 2.0, 3.0, 5.0]) * c + 0.25 * prefix
+        return table[(prefix, c)]
+    return cost
+
+
+@pytest.mark.parametrize("C,p,g", [(96, 3, 2), (96, 4, 2), (1024, 4, 64), (2048, 5, 64), (4096, 8, 64), (640, 5, 64),
+                                   (16384, 8, 64)])
+def test_grid_search_equals_the_oracles_literal_enumeration(C, p, g):
+    cases = [(None, None), (orc.analytic_cost, None), (lambda pr, c: 4.0 + 0.02 * c + 3e-6 * c * (2 * pr + c), None),
+             (orc.analytic_cost, orc.sqrt_rule(C, p, g))]
+    if p <= 5:
+        cases += [(_table_cost(7), None), (_table_cost(8), orc.sqrt_rule(C, p, g))]   # non-monotone, many ties
+    for cost, start in cases:
+        want_b, want_m, _ = orc.hierarchical_grid_search(C, p, g, cost or orc.analytic_cost, start=start)
+        got_b, got_m, evals = kvra.kvra_search_grid(C, p, g, cost, start=start)
+        assert got_b == want_b
+        assert got_m == want_m
+        # memoised per level: at most 25 chunk costs per chunk and level, far below 5^(p-1) * p
+        levels = len(orc.grid_search_strides(C, p, g))
+        assert evals <= p + levels * 25 * p
+
+
+def test_grid_search_argument_checks():
+    with pytest.raises(kvra.KvraError):
+        kvra.kvra_search_grid(100, 4, 64)                       # not on the grid
+    with pytest.raises(kvra.KvraError):
+        kvra.kvra_search_grid(256, 4, 64, start=[0, 64, 64, 192, 256])   # not strictly rising
+    with pytest.raises(kvra.KvraError):
+        kvra.kvra_search_grid(256, 4, 64, start=[0, 64, 100, 192, 256])  # off the grid
+    with pytest.raises(kvra.KvraError):
+        kvra.kvra_search_grid(256, 4, 64, start=[0, 64, 128, 192, 320])  # wrong total
+    with pytest.raises(kvra.KvraError):
+        kvra.kvra_search_grid(256, 4, 64, cost=lambda pr, c: float("nan"))
+    b, m, _ = kvra.kvra_search_grid(256, 4, 64)                 # nowhere to move: stays put
+    assert b == [0, 64, 128, 192, 256]
+    b, m, _ = kvra.kvra_search_grid(640, 1, 64)
+    assert b == [0, 640] and m == orc.analytic_cost(0, 640)
+
+
+@pytest.mark.parametrize("C,g", [(16384, 64), (4096, 64), (1000, 1), (128, 64), (192, 64)])
+def test_two_way_search_equals_full_scan_for_monotone_costs(C, g):
+    for cost in (None, lambda pr, c: 4.0 + 0.02 * c + 3e-6 * c * (2 * pr + c), lambda pr, c: float(c)):
+        want_b, want_m = orc.two_way_scan(C, g, cost or orc.analytic_cost)
+        got_b, got_m, evals = kvra.kvra_search_two_way(C, g, cost)
+        assert got_b == want_b and got_m == want_m
+        assert evals <= 2 * (C // g).bit_length() + 6           # logarithmic, not a scan
+    with pytest.raises(kvra.KvraError):
+        kvra.kvra_search_two_way(64, 64)
+    with pytest.raises(kvra.KvraError):
+        kvra.kvra_search_two_way(200, 64)
+
+
+def test_interpolate_and_table_predict_equal_the_oracle():
+    rnd = random.Random(3)
+    g = 64
+    for p in (2, 4, 8):
+        lens = [4096, 8192, 12288, 16384]
+        table = {}
+        for L in lens:
+            cuts = sorted(rnd.sample(range(1, L // g), p - 1))
+            table[L] = [0] + [g * x for x in cuts] + [L]
+        for C in (2048, 4096, 6144, 10240, 14336, 16384, 20480, 8192 + 64, 12288 - 64):
+            assert kvra.kvra_table_predict(C, g, table) == orc.lookup_partition(C, g, table)
+        assert kvra.kvra_interpolate(10240, g, 8192, table[8192], 12288, table[12288]) == \
+            orc.interpolate_partition(10240, g, 8192, table[8192], 12288, table[12288])
+    # collisions are repaired the same way
+    assert kvra.kvra_interpolate(256, 64, 10000, [0, 10, 20, 9000, 10000], 10000, [0, 10, 20, 9000, 10000]) == \
+        [0, 64, 128, 192, 256]
+    with pytest.raises(kvra.KvraError):
+        kvra.kvra_interpolate(1024, 64, 8192, [0, 4096, 8192], 4096, [0, 2048, 4096])   # len_hi < len_lo
+    with pytest.raises(kvra.KvraError):
+        kvra.kvra_interpolate(1024, 64, 4096, [0, 4096, 4096], 8192, [0, 2048, 8192])   # not rising
+    with pytest.raises(kvra.KvraError):
+        kvra.kvra_interpolate(1000, 64, 4096, [0, 2048, 4096], 8192, [0, 2048, 8192])   # off the grid
