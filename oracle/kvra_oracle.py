@@ -15,11 +15,16 @@ What it defines
     models of Sec. 5 and is fixed here as the half-split "rotate-half" pairing);
   * the dot-product and traffic counts of Sec. 3 / Sec. 4.1 (Eq. 1-6, Fig. 4, Fig. 5);
   * the context-level load-balancing objective of Sec. 4.2 reduced to per-chunk costs:
-    makespan of a partition, even split, exhaustive search.
+    makespan of a partition, even split, exhaustive search; and its search tools: the
+    one-dimensional scan for two processes, the hierarchical grid search, the lookup table
+    with linear interpolation;
+  * the decoder layer a process runs around the attention block (App. C listing: q/k/v and
+    output projections; RMSNorm and the SwiGLU MLP come from the LLaMA models of Sec. 5),
+    exact or with bf16 storage rounding of every intermediate tensor.
 
 Pinned by tests/test_oracle_*.py against hand-computed rationals, closed forms,
-torch's CPU scaled_dot_product_attention, the paper's worked 9-token example and
-brute force.  Parity status: the rotary pairing convention (half-split versus
+torch's CPU scaled_dot_product_attention / rms_norm / silu / linear, the paper's worked
+9-token example, its search example and brute force.  Parity status: the rotary pairing convention (half-split versus
 interleaved) is unpinned by the paper; everything else is pinned.
 """
 from __future__ import annotations
@@ -430,3 +435,75 @@ def lookup_partition(context_len, granularity, table):
     lo = max([x for x in lens if x <= context_len], default=lens[0])
     hi = min([x for x in lens if x >= context_len], default=lens[-1])
     return interpolate_partition(context_len, granularity, lo, table[lo], hi, table[hi])
+
+
+# --------------------------------------------------------------------------- decoder layer
+# What one KV-Runahead process runs per layer around the attention block (Sec. 4.1: every process
+# runs each layer on its own chunk; App. C listing: q/k/v projections before, output projection
+# after the attention).  The paper does not write out the normalisation and the MLP; they are
+# taken from the LLaMA architecture of the models in Sec. 5: pre-norm RMSNorm, no biases,
+# SwiGLU MLP, two residual connections.
+def _no_rounding(t):
+    return t
+
+
+def round_to_bf16(t):
+    """fp64 -> nearest bf16 (ties to even) -> fp64; the storage rounding of a bf16 tensor."""
+    return bf16_bits_to_f64(f64_to_bf16_bits(t))
+
+
+def rms_norm(x, gain, eps):
+    """y[t, :] = x[t, :] / sqrt(mean_j x[t, j]^2 + eps) * gain."""
+    ms = np.mean(x * x, axis=-1, keepdims=True)
+    return x / np.sqrt(ms + eps) * gain
+
+
+def linear(x, w):
+    """y = x w^T for a weight stored [out_features, in_features]; no bias."""
+    return x @ w.T
+
+
+def silu(x):
+    return x / (1.0 + np.exp(-x))
+
+
+def swiglu_mlp(x, w_gate, w_up, w_down, rnd=_no_rounding):
+    act = rnd(silu(linear(x, w_gate)) * linear(x, w_up))
+    return linear(act, w_down)
+
+
+def decoder_layer(x, weights, n_q_heads, n_kv_heads, head_dim, scale, rope_base, eps,
+                  boundaries=None, rnd=_no_rounding):
+    """One pre-norm decoder layer over a whole context x [C, hidden] (fp64).
+
+    weights: dict with 'norm1', 'norm2' [hidden]; 'wq' [H d, hidden]; 'wk', 'wv' [H_kv d, hidden];
+    'wo' [hidden, H d]; 'w_gate', 'w_up' [ffn, hidden]; 'w_down' [hidden, ffn].
+    boundaries: None runs the context in one piece; a partition runs chunk after chunk through the
+    KV-cache (the result is the same: rows of a chunk depend on earlier rows only through K and V).
+    rnd: applied wherever a tensor is stored between two operations; the identity gives the exact
+    layer, round_to_bf16 models bf16 storage of every intermediate.
+    Returns (y [C, hidden], k_cache, v_cache).
+    """
+    C, hidden = x.shape
+    H, Hkv, d = n_q_heads, n_kv_heads, head_dim
+    bounds = [0, C] if boundaries is None else [int(b) for b in boundaries]
+    k_cache = np.zeros((C, Hkv, d))
+    v_cache = np.zeros((C, Hkv, d))
+    y = np.zeros_like(x)
+    for lo, hi in zip(bounds[:-1], bounds[1:]):
+        xc = x[lo:hi]
+        h1 = rnd(rms_norm(xc, weights["norm1"], eps))
+        q = rnd(linear(h1, weights["wq"])).reshape(hi - lo, H, d)
+        k = rnd(linear(h1, weights["wk"])).reshape(hi - lo, Hkv, d)
+        v = rnd(linear(h1, weights["wv"])).reshape(hi - lo, Hkv, d)
+        pos = np.arange(lo, hi)
+        if rope_base is not None:
+            q = rnd(rope(q, pos, rope_base))
+            k = rnd(rope(k, pos, rope_base))
+        k_cache[lo:hi] = k
+        v_cache[lo:hi] = v
+        a = rnd(chunk_attention(q, k_cache, v_cache, lo, hi - lo, scale))
+        x2 = rnd(xc + linear(a.reshape(hi - lo, H * d), weights["wo"]))
+        h2 = rnd(rms_norm(x2, weights["norm2"], eps))
+        y[lo:hi] = rnd(x2 + swiglu_mlp(h2, weights["w_gate"], weights["w_up"], weights["w_down"], rnd))
+    return y, k_cache, v_cache
