@@ -171,6 +171,70 @@ int kvra_interpolate(int64_t context_len, int n_chunks, int64_t granularity,
 int kvra_table_predict(int64_t context_len, int n_chunks, int64_t granularity, int n_entries,
                        const int64_t* entry_lens, const int64_t* entry_bounds, int64_t* boundaries_out);
 
+/*
+ * ---- The decoder layer a process runs around its attention block --------------------------------
+ * Every process runs each layer on its own chunk (Sec. 4.1); the App. C listing shows the q/k/v
+ * projections before and the output projection after the attention.  Normalisation and MLP are not
+ * written out in the paper; they follow the LLaMA architecture of the models in Sec. 5: pre-norm
+ * RMSNorm, no biases, SwiGLU MLP, two residual connections.  All tensors are dense bf16 device
+ * memory; arithmetic is fp32 (MFMA accumulation, norms, activation) with one rounding to bf16 per
+ * stored tensor.
+ */
+
+/* y[t, :] = x[t, :] / sqrt(mean_j x[t, j]^2 + eps) * gain.   x, y: [rows, hidden]; gain: [hidden].
+ * hidden must be a multiple of 8 and at most 8192 (KVRA_EUNSUPPORTED otherwise). */
+int kvra_rms_norm(const void* x, const void* gain, void* y, int64_t rows, int hidden, float eps, void* stream);
+
+/*
+ * Linear layer without bias on the matrix cores: out[m, n] = sum_j x[m, j] * w[n, j]
+ * (weights stored [out_features, in_features]).
+ *   residual != NULL   out = x.w^T + residual            (residual: [m, n]; may alias out)
+ *   w2 != NULL         out = silu(x.w^T) * (x.w2^T)      (the SwiGLU gate and up projections in one pass)
+ * residual and w2 exclude each other (KVRA_EINVAL).  m is free; n must be a multiple of 32 and k of
+ * 64, and x and w must each stay below 4 GiB (KVRA_EUNSUPPORTED).
+ */
+int kvra_linear(const void* x, const void* w, const void* w2, const void* residual, void* out,
+                int64_t m, int64_t n, int64_t k, void* stream);
+
+/*
+ * The three projections of the App. C listing in one launch.  wqkv: [(n_q_heads + 2 n_kv_heads) *
+ * head_dim, k], query rows first, then key rows, then value rows.  q_out [m, n_q_heads, head_dim],
+ * k_out, v_out [m, n_kv_heads, head_dim] are the dense tensors kvra_append_kv takes (un-rotated).
+ */
+int kvra_qkv_proj(const void* x, const void* wqkv, void* q_out, void* k_out, void* v_out,
+                  int64_t m, int n_q_heads, int n_kv_heads, int head_dim, int64_t k, void* stream);
+
+typedef struct {
+  int hidden, ffn, n_q_heads, n_kv_heads, head_dim;
+  float rms_eps;       /* 1e-6 for the LLaMA shapes                                    */
+  float rope_base;     /* <= 0 disables the rotary embedding                             */
+  float scale;         /* softmax scale, 1/sqrt(head_dim) by convention                  */
+  const void* norm1;   /* [hidden]                                                       */
+  const void* wqkv;    /* [(n_q_heads + 2 n_kv_heads) head_dim, hidden]                  */
+  const void* wo;      /* [hidden, n_q_heads head_dim]                                   */
+  const void* norm2;   /* [hidden]                                                       */
+  const void* w_gate;  /* [ffn, hidden]                                                  */
+  const void* w_up;    /* [ffn, hidden]                                                  */
+  const void* w_down;  /* [hidden, ffn]                                                  */
+} kvra_layer;
+
+/* Bytes of device workspace kvra_layer_chunk needs for a chunk of this length (-1: bad layer). */
+int64_t kvra_layer_workspace_bytes(const kvra_layer* layer, int64_t chunk_len);
+
+/*
+ * One layer over one chunk: RMSNorm, q/k/v projections, kvra_append_kv (rotary embedding + cache
+ * rows [prefix_len, prefix_len + chunk_len)), kvra_chunk_attn, output projection + residual,
+ * RMSNorm, SwiGLU MLP + residual; eight launches on `stream`.
+ *   x, y        [chunk_len, hidden]; y may not alias x
+ *   workspace   caller-owned device memory, 256-byte aligned, at least
+ *               kvra_layer_workspace_bytes(layer, chunk_len); contents are scratch
+ * Errors: as the calls it is made of; KVRA_EINVAL for a short or misaligned workspace.  hidden and
+ * ffn must be multiples of 64.
+ */
+int kvra_layer_chunk(const kvra_layer* layer, const void* x, void* y, void* k_cache, void* v_cache,
+                     int64_t prefix_len, int64_t chunk_len, int64_t capacity,
+                     void* workspace, int64_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

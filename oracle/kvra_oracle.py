@@ -473,7 +473,7 @@ def swiglu_mlp(x, w_gate, w_up, w_down, rnd=_no_rounding):
 
 
 def decoder_layer(x, weights, n_q_heads, n_kv_heads, head_dim, scale, rope_base, eps,
-                  boundaries=None, rnd=_no_rounding):
+                  boundaries=None, rnd=_no_rounding, trace=None):
     """One pre-norm decoder layer over a whole context x [C, hidden] (fp64).
 
     weights: dict with 'norm1', 'norm2' [hidden]; 'wq' [H d, hidden]; 'wk', 'wv' [H_kv d, hidden];
@@ -482,6 +482,8 @@ def decoder_layer(x, weights, n_q_heads, n_kv_heads, head_dim, scale, rope_base,
     KV-cache (the result is the same: rows of a chunk depend on earlier rows only through K and V).
     rnd: applied wherever a tensor is stored between two operations; the identity gives the exact
     layer, round_to_bf16 models bf16 storage of every intermediate.
+    trace: an optional dict that receives the intermediate 'x2' [C, hidden] (input plus attention
+    branch), which tests need to scale their error bounds.
     Returns (y [C, hidden], k_cache, v_cache).
     """
     C, hidden = x.shape
@@ -504,6 +506,8 @@ def decoder_layer(x, weights, n_q_heads, n_kv_heads, head_dim, scale, rope_base,
         v_cache[lo:hi] = v
         a = rnd(chunk_attention(q, k_cache, v_cache, lo, hi - lo, scale))
         x2 = rnd(xc + linear(a.reshape(hi - lo, H * d), weights["wo"]))
+        if trace is not None:
+            trace.setdefault("x2", np.zeros_like(x))[lo:hi] = x2
         h2 = rnd(rms_norm(x2, weights["norm2"], eps))
         y[lo:hi] = rnd(x2 + swiglu_mlp(h2, weights["w_gate"], weights["w_up"], weights["w_down"], rnd))
     return y, k_cache, v_cache

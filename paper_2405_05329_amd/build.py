@@ -11,7 +11,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libkvra.so")
 
-SOURCES = ["kvra_api.hip", "kvra_append.hip", "kvra_attn.hip", "kvra_balance.cpp", "kvra_search.cpp"]
+SOURCES = ["kvra_api.hip", "kvra_append.hip", "kvra_attn.hip", "kvra_gemm.hip", "kvra_balance.cpp", "kvra_search.cpp"]
 
 # packed fp32 VALU ops are switched off for every device translation unit
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -19,6 +19,16 @@ int launch_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
                       int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_kv_heads, int head_dim,
                       float scale, void* out, hipStream_t stream);
 
+// out[m, n_out] = x[m, k] . w[n_out, k]^T (+ residual), or silu(x . w^T) * (x . w2^T) when w2 is given.
+// The n_out output columns are split over n_seg (1..3) dense matrices of seg_cols[s] columns each.
+int launch_linear(const void* x, const void* w, const void* w2, const void* residual,
+                  void* const* out, const int* seg_cols, int n_seg,
+                  int64_t m, int64_t n_out, int64_t k, hipStream_t stream);
+
+int launch_rms_norm(const void* x, const void* gain, void* y, int64_t rows, int hidden, float eps,
+                    hipStream_t stream);
+int rms_norm_max_hidden();
+
 // Launch with the runtime's own status as the result.  (hipGetLastError would also pick up
 // stale, unrelated codes that other users of the runtime in this thread left behind.)
 template <typename Args>

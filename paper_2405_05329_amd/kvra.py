@@ -63,7 +63,27 @@ def _load() -> ctypes.CDLL:
     lib.kvra_interpolate.argtypes = [i64, i32, i64, i64, pi64, i64, pi64, pi64]
     lib.kvra_table_predict.restype = i32
     lib.kvra_table_predict.argtypes = [i64, i32, i64, i32, pi64, pi64, pi64]
+    lib.kvra_rms_norm.restype = i32
+    lib.kvra_rms_norm.argtypes = [vp, vp, vp, i64, i32, f32, vp]
+    lib.kvra_linear.restype = i32
+    lib.kvra_linear.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp]
+    lib.kvra_qkv_proj.restype = i32
+    lib.kvra_qkv_proj.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, i32, i64, vp]
+    lib.kvra_layer_workspace_bytes.restype = i64
+    lib.kvra_layer_workspace_bytes.argtypes = [ctypes.POINTER(KvraLayer), i64]
+    lib.kvra_layer_chunk.restype = i32
+    lib.kvra_layer_chunk.argtypes = [ctypes.POINTER(KvraLayer), vp, vp, vp, vp, i64, i64, i64, vp, i64, vp]
     return lib
+
+
+class KvraLayer(ctypes.Structure):
+    """Mirror of the C struct kvra_layer."""
+    _fields_ = [("hidden", ctypes.c_int), ("ffn", ctypes.c_int), ("n_q_heads", ctypes.c_int),
+                ("n_kv_heads", ctypes.c_int), ("head_dim", ctypes.c_int),
+                ("rms_eps", ctypes.c_float), ("rope_base", ctypes.c_float), ("scale", ctypes.c_float),
+                ("norm1", ctypes.c_void_p), ("wqkv", ctypes.c_void_p), ("wo", ctypes.c_void_p),
+                ("norm2", ctypes.c_void_p), ("w_gate", ctypes.c_void_p), ("w_up", ctypes.c_void_p),
+                ("w_down", ctypes.c_void_p)]
 
 
 _lib = _load()
@@ -224,3 +244,47 @@ def kvra_table_predict(context_len, granularity, table):
     if rc != KVRA_OK:
         raise KvraError(rc, "kvra_table_predict")
     return list(out)
+
+
+def kvra_rms_norm(x, gain, y, rows, hidden, eps, stream=None):
+    rc = _lib.kvra_rms_norm(_ptr(x), _ptr(gain), _ptr(y), int(rows), int(hidden), float(eps), _stream(stream))
+    if rc != KVRA_OK:
+        raise KvraError(rc, "kvra_rms_norm")
+
+
+def kvra_linear(x, w, w2, residual, out, m, n, k, stream=None):
+    rc = _lib.kvra_linear(_ptr(x), _ptr(w), _ptr(w2), _ptr(residual), _ptr(out), int(m), int(n), int(k),
+                          _stream(stream))
+    if rc != KVRA_OK:
+        raise KvraError(rc, "kvra_linear")
+
+
+def kvra_qkv_proj(x, wqkv, q_out, k_out, v_out, m, n_q_heads, n_kv_heads, head_dim, k, stream=None):
+    rc = _lib.kvra_qkv_proj(_ptr(x), _ptr(wqkv), _ptr(q_out), _ptr(k_out), _ptr(v_out), int(m), int(n_q_heads),
+                            int(n_kv_heads), int(head_dim), int(k), _stream(stream))
+    if rc != KVRA_OK:
+        raise KvraError(rc, "kvra_qkv_proj")
+
+
+def make_layer(hidden, ffn, n_q_heads, n_kv_heads, head_dim, rms_eps, rope_base, scale,
+               norm1, wqkv, wo, norm2, w_gate, w_up, w_down) -> KvraLayer:
+    """Fills a kvra_layer from device tensors (or raw pointers); the caller keeps the tensors alive."""
+    return KvraLayer(int(hidden), int(ffn), int(n_q_heads), int(n_kv_heads), int(head_dim),
+                     float(rms_eps), float(rope_base), float(scale),
+                     _ptr(norm1), _ptr(wqkv), _ptr(wo), _ptr(norm2), _ptr(w_gate), _ptr(w_up), _ptr(w_down))
+
+
+def kvra_layer_workspace_bytes(layer: KvraLayer, chunk_len) -> int:
+    n = _lib.kvra_layer_workspace_bytes(ctypes.byref(layer), int(chunk_len))
+    if n < 0:
+        raise KvraError(KVRA_EINVAL, "kvra_layer_workspace_bytes")
+    return n
+
+
+def kvra_layer_chunk(layer: KvraLayer, x, y, k_cache, v_cache, prefix_len, chunk_len, capacity,
+                     workspace, workspace_bytes, stream=None):
+    rc = _lib.kvra_layer_chunk(ctypes.byref(layer), _ptr(x), _ptr(y), _ptr(k_cache), _ptr(v_cache),
+                               int(prefix_len), int(chunk_len), int(capacity), _ptr(workspace),
+                               int(workspace_bytes), _stream(stream))
+    if rc != KVRA_OK:
+        raise KvraError(rc, "kvra_layer_chunk")

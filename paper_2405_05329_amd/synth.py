@@ -61,3 +61,29 @@ def make_qkv(seed: int, cfg_id: int, C: int, H: int, Hkv: int, d: int, q_gain: f
 
 def default_scale(d: int) -> float:
     return 1.0 / math.sqrt(d)
+
+
+# Decoder-layer shapes (hidden, ffn) that go with the attention shapes above; the weights of the
+# pretrained models are not available, so Gaussians of the usual initialisation width stand in.
+LAYER_SHAPES = {
+    "llama7b": dict(hidden=4096, ffn=11008, H=32, Hkv=32, d=128, weight_std=0.02),
+}
+RMS_EPS = 1e-6
+
+
+def make_layer_weights(seed: int, cfg_id: int, hidden: int, ffn: int, H: int, Hkv: int, d: int,
+                       weight_std: float):
+    """bf16 bit patterns of one layer's parameters: norm gains ~ 1 + N(0, 0.1^2), matrices
+    ~ N(0, weight_std^2), stored [out_features, in_features]; wqkv = query rows, key rows, value rows."""
+    def mat(tid, rows, cols):
+        return normal_bf16(seed, cfg_id, tid, (rows, cols), std=weight_std)
+    def gain(tid):
+        rng = np.random.default_rng([seed, cfg_id, tid])
+        return f32_to_bf16_bits(1.0 + 0.1 * rng.standard_normal(size=hidden, dtype=np.float32))
+    return {
+        "norm1": gain(10), "norm2": gain(11),
+        "wqkv": mat(12, (H + 2 * Hkv) * d, hidden),
+        "wo": mat(13, hidden, H * d),
+        "w_gate": mat(14, ffn, hidden), "w_up": mat(15, ffn, hidden),
+        "w_down": mat(16, hidden, ffn),
+    }
