@@ -64,6 +64,123 @@ def cpu_baseline(cfg, sample_heads=8):
             "seconds": dt}
 
 
+def layer_bench(args):
+    """--layer: one step = the decoder layer (kvra_layer_chunk: RMSNorm, q/k/v projections, append,
+    attention, output projection, RMSNorm, SwiGLU MLP) over the 8 balanced chunks of the 32k-token
+    Llama-7B shape.  Not the headline metric; printed in the same one-line form."""
+    import torch
+    from paper_2405_05329_amd import kvra, synth
+
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.workload]
+    shp = synth.LAYER_SHAPES["llama7b"]
+    C, H, Hkv, d = cfg["C"], cfg["H"], cfg["Hkv"], cfg["d"]
+    assert (H, Hkv, d) == (shp["H"], shp["Hkv"], shp["d"]), "layer bench needs a Llama-7B-shaped workload"
+    hidden, ffn = shp["hidden"], shp["ffn"]
+    bounds = cfg["boundaries"]
+    p = len(bounds) - 1
+    scale = synth.default_scale(d)
+
+    def dev(bits):
+        return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+    wt = {k: dev(v) for k, v in synth.make_layer_weights(0, cfg["cfg_id"], hidden, ffn, H, Hkv, d,
+                                                         shp["weight_std"]).items()}
+    layer = kvra.make_layer(hidden, ffn, H, Hkv, d, synth.RMS_EPS, synth.ROPE_BASE, scale, wt["norm1"], wt["wqkv"],
+                            wt["wo"], wt["norm2"], wt["w_gate"], wt["w_up"], wt["w_down"])
+    x = dev(synth.normal_bf16(0, cfg["cfg_id"], 0, (C, hidden)))
+    y = torch.empty_like(x)
+    k_cache = torch.zeros((C, Hkv, d), dtype=torch.bfloat16, device="cuda")
+    v_cache = torch.zeros_like(k_cache)
+    cmax = max(bounds[i + 1] - bounds[i] for i in range(p))
+    nbytes = kvra.kvra_layer_workspace_bytes(layer, cmax)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def run_step(events=None):
+        for i in range(p):
+            lo, hi = bounds[i], bounds[i + 1]
+            if events is not None:
+                events[i][0].record(stream)
+            kvra.kvra_layer_chunk(layer, x[lo:hi], y[lo:hi], k_cache, v_cache, lo, hi - lo, C, ws, nbytes,
+                                  stream=stream)
+            if events is not None:
+                events[i][1].record(stream)
+
+    for _ in range(args.warmup):
+        run_step()
+    ev = [[[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(p)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        run_step(ev[s])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    chunk_ms = np.array([[e[0].elapsed_time(e[1]) for e in step] for step in ev]).mean(axis=0)
+    qkv_rows = (H + 2 * Hkv) * d
+    lin_per_token = 2 * (hidden * qkv_rows + hidden * H * d + 3 * hidden * ffn)
+    attn_flops = [useful_flops(bounds[i], bounds[i + 1] - bounds[i], H, d) for i in range(p)]
+    lin_flops = [lin_per_token * (bounds[i + 1] - bounds[i]) for i in range(p)]
+    total = sum(attn_flops) + sum(lin_flops)
+
+    # per-operator times of the first chunk, same launches issued one by one
+    lo, hi = bounds[0], bounds[1]
+    c = hi - lo
+    h = torch.empty((c, hidden), dtype=torch.bfloat16, device="cuda")
+    q = torch.empty((c, H, d), dtype=torch.bfloat16, device="cuda")
+    kk = torch.empty((c, Hkv, d), dtype=torch.bfloat16, device="cuda")
+    vv = torch.empty_like(kk)
+    att = torch.empty_like(q)
+    x2 = torch.empty_like(h)
+    act = torch.empty((c, ffn), dtype=torch.bfloat16, device="cuda")
+    ops = [
+        ("rms_norm", lambda: kvra.kvra_rms_norm(x[lo:hi], wt["norm1"], h, c, hidden, synth.RMS_EPS), 0),
+        ("qkv_proj", lambda: kvra.kvra_qkv_proj(h, wt["wqkv"], q, kk, vv, c, H, Hkv, d, hidden), 2 * c * hidden * qkv_rows),
+        ("append_kv", lambda: kvra.kvra_append_kv(kk, vv, q, k_cache, v_cache, lo, c, C, H, Hkv, d, synth.ROPE_BASE), 0),
+        ("chunk_attn", lambda: kvra.kvra_chunk_attn(q, k_cache, v_cache, lo, c, H, Hkv, d, scale, att), attn_flops[0]),
+        ("out_proj+res", lambda: kvra.kvra_linear(att, wt["wo"], None, x[lo:hi], x2, c, hidden, H * d), 2 * c * hidden * H * d),
+        ("gate_up+swiglu", lambda: kvra.kvra_linear(h, wt["w_gate"], wt["w_up"], None, act, c, ffn, hidden), 4 * c * hidden * ffn),
+        ("down_proj+res", lambda: kvra.kvra_linear(act, wt["w_down"], None, x2, y[lo:hi], c, hidden, ffn), 2 * c * hidden * ffn),
+    ]
+    breakdown = {}
+    lin_ms, lin_fl = 0.0, 0
+    for name, fn, fl in ops:
+        for _ in range(2):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(5):
+            fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 5
+        breakdown[name] = {"ms": round(ms, 4), "tflops": round(fl / ms / 1e9, 1) if fl else None}
+        if name in ("qkv_proj", "out_proj+res", "gate_up+swiglu", "down_proj+res"):
+            lin_ms += ms
+            lin_fl += fl
+    achieved = lin_fl / lin_ms / 1e9
+    result = {
+        "metric": "decoder-layer TFLOP/s (useful FLOPs: causal attention + linear layers), chunked prefill",
+        "value": total / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload + "+layer", "context_len": C, "hidden": hidden, "ffn": ffn,
+                   "n_q_heads": H, "n_kv_heads": Hkv, "head_dim": d, "chunks": p, "boundaries": bounds,
+                   "useful_gflop_per_step": total / 1e9},
+        "pct_of_bf16_peak": 100.0 * total / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "roofline": {"kernel": "linear_kernel", "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "note": "the four linear launches of chunk 0, algorithmic FLOPs / summed launch time"},
+        "per_chunk": {"layer_ms": [round(float(v), 4) for v in chunk_ms],
+                      "layer_tflops": [round((attn_flops[i] + lin_flops[i]) / chunk_ms[i] / 1e9, 1) for i in range(p)]},
+        "chunk0_breakdown": breakdown,
+        "makespan": {"balanced_ms": float(chunk_ms.max())},
+        "cpu_baseline": None,
+    }
+    print(json.dumps(result))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -73,6 +190,8 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="skip the equal-split comparison runs")
     ap.add_argument("--workload", default=WORKLOAD,
                     help="a key of synth.CONFIGS; the default is the workload the metric is quoted on")
+    ap.add_argument("--layer", action="store_true",
+                    help="time the whole decoder layer per chunk (use with --workload llama7b_32k_balanced)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also issue one plain 256 MiB device-to-device copy (outside the timed region) so "
                          "that a rocprofv3 --pmc run holds a dispatch of known traffic to scale counters by")
@@ -88,6 +207,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(1)
+    if args.layer:
+        layer_bench(args)
+        return
     torch.cuda.set_device(0)
     cfg = synth.CONFIGS[args.workload]
     C, H, Hkv, d = cfg["C"], cfg["H"], cfg["Hkv"], cfg["d"]
