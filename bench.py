@@ -160,6 +160,56 @@ def layer_bench(args):
             lin_ms += ms
             lin_fl += fl
     achieved = lin_fl / lin_ms / 1e9
+
+    # context-level load balancing with the whole layer as the cost (Sec. 4.2): fit
+    # t = a + b c + e c (2 prefix + c) to measured layer times and let kvra_balance cut the context
+    makespan = {"attention_balanced_ms": float(chunk_ms.max())}
+    if not args.no_extras:
+        def layer_ms(prefix, c, reps=2):
+            best = float("inf")
+            for _ in range(reps):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                kvra.kvra_layer_chunk(layer, x[prefix:prefix + c], y[prefix:prefix + c], k_cache, v_cache, prefix, c, C,
+                                      ws, nbytes, stream=stream)
+                e1.record(stream)
+                torch.cuda.synchronize()
+                best = min(best, e0.elapsed_time(e1))
+            return best
+        table = {}
+        for pr in (0, 8192, 16384, 24576, 30720):
+            for c in (512, 1024, 2048, 4096, 8192, cmax):
+                if pr + c <= C:
+                    table[(pr, c)] = layer_ms(pr, c)
+        A = np.array([[1.0, c, c * (2 * pr + c)] for (pr, c) in table])
+        coef, *_ = np.linalg.lstsq(A, np.array(list(table.values())), rcond=None)
+        cost = lambda prefix, c: float(coef[0] + coef[1] * c + coef[2] * c * (2 * prefix + c))
+        def measured(bnds):
+            cm = max(bnds[i + 1] - bnds[i] for i in range(len(bnds) - 1))
+            if cm > cmax:
+                return None
+            acc = np.zeros(len(bnds) - 1)
+            for rep in range(3):
+                for i in range(len(bnds) - 1):
+                    lo_, hi_ = bnds[i], bnds[i + 1]
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(stream)
+                    kvra.kvra_layer_chunk(layer, x[lo_:hi_], y[lo_:hi_], k_cache, v_cache, lo_, hi_ - lo_, C, ws, nbytes,
+                                          stream=stream)
+                    e1.record(stream)
+                    torch.cuda.synchronize()
+                    if rep:
+                        acc[i] += e0.elapsed_time(e1)
+            return float((acc / 2).max())
+        bal, pred = kvra.kvra_balance(C, p, 64, cost)
+        eq = kvra.kvra_equal_split(C, p, 64)
+        makespan.update({
+            "cost_fit_ms": {"const": float(coef[0]), "per_token": float(coef[1]), "per_causal_area": float(coef[2])},
+            "layer_balanced_boundaries": bal, "layer_balanced_predicted_ms": pred,
+            "layer_balanced_measured_ms": measured(bal),
+            "equal_split_measured_ms": measured(eq),
+            "layer_balanced_first_chunk_share": bal[1] / C, "attention_balanced_first_chunk_share": bounds[1] / C,
+        })
     result = {
         "metric": "decoder-layer TFLOP/s (useful FLOPs: causal attention + linear layers), chunked prefill",
         "value": total / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s",
@@ -175,7 +225,7 @@ def layer_bench(args):
         "per_chunk": {"layer_ms": [round(float(v), 4) for v in chunk_ms],
                       "layer_tflops": [round((attn_flops[i] + lin_flops[i]) / chunk_ms[i] / 1e9, 1) for i in range(p)]},
         "chunk0_breakdown": breakdown,
-        "makespan": {"balanced_ms": float(chunk_ms.max())},
+        "makespan": makespan,
         "cpu_baseline": None,
     }
     print(json.dumps(result))
