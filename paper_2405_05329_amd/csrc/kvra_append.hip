@@ -32,14 +32,16 @@ __device__ __forceinline__ unsigned short f32_to_bf16_rne(float x) {
   return static_cast<unsigned short>(u >> 16);
 }
 
-// One workgroup serves TOK consecutive tokens.  Phase 1: TOK * D/2 threads form cos/sin of
-// (prefix + row) * inv_freq[i] in fp64 and park them in LDS as fp32.  Phase 2: all threads
-// stream "pair units" (a 16-byte piece of the low half of a head row and its partner in the
-// high half) for K and Q, and plain 16-byte pieces for V.
-template <int D>
+// One workgroup serves TOK consecutive tokens (TOK * D/2 <= 256).  Phase 1: TOK * D/2 threads form
+// cos/sin of (prefix + row) * inv_freq[i] in fp64 and park them in LDS as fp32.  Phase 2: all
+// threads stream "pair units" (a 16-byte piece of the low half of a head row and its partner in
+// the high half) for K and Q, and plain 16-byte pieces for V.  Long chunks use the largest TOK
+// (every thread busy in phase 1); short chunks use fewer tokens per workgroup so that the launch
+// still puts several workgroups on every CU.
+template <int D, int TOK>
 __global__ __launch_bounds__(256) void append_kv_kernel(AppendArgs a) {
   constexpr int HALF = D / 2;
-  constexpr int TOK = 256 / HALF;          // 4 tokens (D=128) or 8 tokens (D=64)
+  static_assert(TOK * HALF <= 256, "one thread per (token, frequency) in phase 1");
   constexpr int PAIRS = D / 16;            // pair units per head row
   constexpr int CHUNKS = D / 8;            // 16-byte pieces per head row
   __shared__ float cs[TOK][HALF];
@@ -48,6 +50,19 @@ __global__ __launch_bounds__(256) void append_kv_kernel(AppendArgs a) {
   const int tid = threadIdx.x;
   const int tok0 = blockIdx.x * TOK;
   const int ntok = min(TOK, a.chunk_len - tok0);
+
+  const int Hkv = a.n_kv_heads, H = a.n_q_heads;
+
+  // ---- V: bit-exact copy, issued first: it needs no angles, and its traffic overlaps the
+  // fp64 sincos below -------------------------------------------------------------------
+  {
+    const int per_tok = Hkv * CHUNKS;
+    const int total = ntok * per_tok;
+    const u16x8* src = reinterpret_cast<const u16x8*>(a.v_in) + static_cast<long long>(tok0) * per_tok;
+    u16x8* dst = reinterpret_cast<u16x8*>(a.v_cache) + (a.prefix_len + tok0) * per_tok;
+#pragma unroll 4
+    for (int u = tid; u < total; u += 256) dst[u] = src[u];
+  }
 
   if (a.use_rope) {
     const int t = tid / HALF, i = tid % HALF;
@@ -59,18 +74,6 @@ __global__ __launch_bounds__(256) void append_kv_kernel(AppendArgs a) {
       sn[t][i] = static_cast<float>(s);
     }
     __syncthreads();
-  }
-
-  const int Hkv = a.n_kv_heads, H = a.n_q_heads;
-
-  // ---- V: bit-exact copy -------------------------------------------------------------
-  {
-    const int per_tok = Hkv * CHUNKS;
-    const int total = ntok * per_tok;
-    const u16x8* src = reinterpret_cast<const u16x8*>(a.v_in) + static_cast<long long>(tok0) * per_tok;
-    u16x8* dst = reinterpret_cast<u16x8*>(a.v_cache) + (a.prefix_len + tok0) * per_tok;
-#pragma unroll 4
-    for (int u = tid; u < total; u += 256) dst[u] = src[u];
   }
 
   // ---- K: rotate (or copy) into the cache --------------------------------------------
@@ -148,10 +151,21 @@ int launch_append_kv(const void* k_in, const void* v_in, void* q_inout, void* k_
     for (int i = 0; i < head_dim / 2; ++i)
       a.inv_freq[i] = std::pow(static_cast<double>(rope_base), -2.0 * i / head_dim);
   }
-  const int tok_per_wg = 256 / (head_dim / 2);
-  const unsigned grid = static_cast<unsigned>((chunk_len + tok_per_wg - 1) / tok_per_wg);
-  if (head_dim == 128) return launch_kernel(append_kv_kernel<128>, dim3(grid), dim3(256), a, stream);
-  return launch_kernel(append_kv_kernel<64>, dim3(grid), dim3(256), a, stream);
+  // tokens per workgroup: the most that phase 1 can serve, halved until the grid holds about
+  // eight workgroups per CU (256 CUs) or one token per workgroup is reached
+  int tok = 256 / (head_dim / 2);
+  while (tok > 1 && (chunk_len + tok - 1) / tok < 2048) tok >>= 1;
+  const unsigned grid = static_cast<unsigned>((chunk_len + tok - 1) / tok);
+  const dim3 g(grid), b(256);
+  if (head_dim == 128) {
+    if (tok == 4) return launch_kernel(append_kv_kernel<128, 4>, g, b, a, stream);
+    if (tok == 2) return launch_kernel(append_kv_kernel<128, 2>, g, b, a, stream);
+    return launch_kernel(append_kv_kernel<128, 1>, g, b, a, stream);
+  }
+  if (tok == 8) return launch_kernel(append_kv_kernel<64, 8>, g, b, a, stream);
+  if (tok == 4) return launch_kernel(append_kv_kernel<64, 4>, g, b, a, stream);
+  if (tok == 2) return launch_kernel(append_kv_kernel<64, 2>, g, b, a, stream);
+  return launch_kernel(append_kv_kernel<64, 1>, g, b, a, stream);
 }
 
 }  // namespace kvra
