@@ -219,3 +219,19 @@ def test_paper_shapes_sampled_rows(name, n_random):
     G = cfg["H"] // cfg["Hkv"]
     vmax = np.abs(_f64(v)).max(axis=0)            # [Hkv, d]
     assert np.all(np.abs(out) <= np.repeat(vmax, G, axis=0)[None] * (1 + 2 ** -7))
+
+
+def test_long_context_sampled_rows():
+    """A quarter-million-token context (MQA, 4 query heads on one KV head): large prefix, positions
+    far beyond the workloads above, thousands of row tiles per KV head; checked on sampled rows."""
+    C, H, Hkv, d = 262144, 4, 1, 128
+    bounds = [0, 261000, 261001, C]
+    q, k, v, scale, res = _run(31, 0, C, H, Hkv, d, bounds)
+    rng = np.random.default_rng(5)
+    rows = sorted({0, 1, 63, 64, 255, 256, 260999, 261000, 261001, 261002, C - 1}
+                  | {int(x) for x in rng.integers(0, C, size=12)})
+    want = orc.attention_rows(_f64(q), _f64(k), _f64(v), rows, scale, rope_base=synth.ROPE_BASE)
+    mx, mean = _check_out(res["out"][rows], want, "long context")
+    print(f"long context: {len(rows)} rows: max-abs {mx:.3e} mean-abs {mean:.3e}")
+    np.testing.assert_array_equal(res["v_cache"], v)
+    assert np.all(np.isfinite(_f64(res["out"])))
