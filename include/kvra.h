@@ -15,8 +15,11 @@
  *   - Return value: KVRA_OK, or a negative code; on error nothing was enqueued.
  *   - head_dim must be 64 or 128; n_q_heads must be a multiple of n_kv_heads; query head h
  *     reads key/value head h / (n_q_heads / n_kv_heads).
- *   - No entry point allocates device memory or keeps state between calls: every intermediate
- *     of kvra_chunk_attn lives in registers and LDS, so calls on different streams may overlap.
+ *   - The only state the library keeps is one scratch buffer per device (about 70 MB, hipMalloc'ed
+ *     by the first kvra_chunk_attn call on that device, kept until the process ends).  It holds
+ *     the partial results of key-split launches; two kvra_chunk_attn calls (kvra_layer_chunk
+ *     included) that overlap in time on one device, from different streams, would share it and
+ *     are not supported.  If the allocation fails the call runs without key-splitting.
  */
 #ifndef KVRA_H
 #define KVRA_H

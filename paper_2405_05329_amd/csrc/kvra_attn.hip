@@ -19,8 +19,17 @@
 // d = 128) and a VALU block (softmax of this tile, staging of future K/V tiles), with a workgroup
 // barrier after each block.  The second group starts one barrier late, so while one group keeps
 // the matrix pipe busy its SIMD partner does exp2/max/sum on the vector ALU ("ping-pong").
+//
+// Launch shapes.  Normally one workgroup per unit (kv head, 256-row tile), every unit whole.  When
+// the units would fill the CUs unevenly (160 or 320 units on 256 CUs; a handful of very long units
+// for a short chunk behind a long prefix) the launch is key-split instead: one workgroup per CU
+// takes an equal run of the key-tile steps of all units laid end to end, whole units are finished
+// in place, and the pieces of the units that a cut falls into go through a per-device scratch
+// buffer to a small fix-up kernel that merges them (the usual log-sum-exp merge).
 #include "kvra_internal.h"
 
+#include <algorithm>
+#include <mutex>
 #include <type_traits>
 
 namespace kvra {
@@ -40,6 +49,7 @@ constexpr int kThreads = 64 * kWaves;
 constexpr int kBN = 64;                // keys per tile
 constexpr int kStages = 3;             // LDS ring depth for K and for V tiles
 constexpr float kRescaleSlack = 8.0f;  // exponent headroom (log2) before the running max is moved
+constexpr float kNoKeyYet = -1e30f;    // exponent reference of a row before its first visible key
 
 struct AttnArgs {
   const __bf16* q;
@@ -54,7 +64,32 @@ struct AttnArgs {
   int nq_tiles;      // row tiles per kv head
   int rows_per_wg;   // virtual rows per workgroup: 32 * (active waves), <= 256
   float c_log2;      // scale * log2(e): softmax runs in base 2
+  // key-split ("stream-K") launches only
+  float* scratch;    // partial results, 2 slots per workgroup
+  int sk_groups;     // workgroup / unit groups (8 = one per XCD when Hkv % 8 == 0, else 1)
+  int sk_wgs;        // workgroups per group
 };
+
+// Work units of a launch.  Unit = (kv head g, row tile qt); the units of group x, in order
+// j = 0, 1, ..: g = x + groups * (j % hp), qt = nq_tiles - 1 - j / hp, hp = Hkv / groups heads per
+// group (longest row tiles first).  A unit walks unit_steps(qt) key tiles.
+__device__ __forceinline__ int unit_row_hi(const AttnArgs& a, int qt) {
+  return min((qt + 1) * a.rows_per_wg, a.chunk * a.G);   // exclusive, in virtual rows
+}
+__device__ __forceinline__ int unit_steps(const AttnArgs& a, int qt) {
+  return (a.prefix + (unit_row_hi(a, qt) - 1) / a.G) / kBN + 1;
+}
+// Key-split schedule: the key-tile steps of a group's units, laid end to end, are cut into sk_wgs
+// equal runs; workgroup i of the group takes steps [sk_cut(T, i), sk_cut(T, i + 1)).
+__device__ __forceinline__ long long sk_cut(long long total_steps, int i, int wgs) {
+  return total_steps * i / wgs;
+}
+__device__ __forceinline__ long long sk_group_steps(const AttnArgs& a) {
+  long long t = 0;
+  for (int qt = 0; qt < a.nq_tiles; ++qt) t += unit_steps(a, qt);
+  return t * (a.Hkv / a.sk_groups);
+}
+constexpr int kPartialFloats(int D) { return kWaves * (D / 32 * 16 + 2) * 64; }   // per scratch slot
 
 __device__ __forceinline__ float other_half(float x) {
   // value held by lane ^ 32
@@ -74,8 +109,12 @@ __device__ __forceinline__ void lds_dma16(const void* uniform_base, unsigned lan
                : "memory", "m0");
 }
 
+// One fragment of work: the queries of row tile qt of kv head g against key tiles [jt0, jt1).
+// partial == nullptr: the fragment covers all the keys the tile needs, O / l goes to a.out.
+// Otherwise the un-normalised state (O, m, l per lane) goes to partial for the fix-up kernel.
 template <int D>
-__global__ __launch_bounds__(kThreads, 1) void chunk_attn_kernel(AttnArgs a) {
+__device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, const int g, const int qt,
+                                       const int jt0, const int jt1, float* partial) {
   constexpr int BN = kBN;
   constexpr int CPR = D / 8;               // 16-byte pieces per K/V row
   constexpr int KS = D / 16;               // contraction steps of S^T = K Q^T
@@ -86,7 +125,7 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_attn_kernel(AttnArgs a) {
   constexpr int PF = 4;                    // LDS operand reads kept in flight ahead of the MFMAs
   static_assert(TILE % kThreads == 0, "tile must split evenly over the workgroup");
 
-  extern __shared__ u32x4 smem[];          // K ring then V ring, kStages tiles each
+  // smem: K ring then V ring, kStages tiles each
   auto ldsK = [&](int b) -> u32x4* { return smem + b * TILE; };
   auto ldsV = [&](int b) -> u32x4* { return smem + (kStages + b) * TILE; };
 
@@ -94,22 +133,6 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_attn_kernel(AttnArgs a) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction
   const int n = lane & 31, kg = lane >> 5;
   const int phase = wave >> 2;             // 0: first group, 1: second group (one barrier late)
-
-  // workgroup -> (kv head, row tile): longest row tiles first; with Hkv a multiple of 8 the
-  // heads are dealt to the 8 XCDs (workgroup ids go round-robin over XCDs) so that each
-  // XCD's L2 holds the K/V stream of its own heads only.
-  int g, qt;
-  {
-    const int bid = blockIdx.x;
-    if ((a.Hkv & 7) == 0) {
-      const int xcd = bid & 7, j = bid >> 3, hp = a.Hkv >> 3;
-      g = xcd + 8 * (j % hp);
-      qt = a.nq_tiles - 1 - j / hp;
-    } else {
-      g = bid % a.Hkv;
-      qt = a.nq_tiles - 1 - bid / a.Hkv;
-    }
-  }
 
   const int VR = a.chunk * a.G;            // virtual rows of this kv head
   const int total = a.prefix + a.chunk;    // valid cache rows
@@ -125,8 +148,9 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_attn_kernel(AttnArgs a) {
   const int qpos = a.prefix + r;
   const int wmin = a.prefix + min(v0, row_hi - 1) / a.G;        // wave-uniform
   const int wmax = a.prefix + min(v0 + 31, row_hi - 1) / a.G;   // wave-uniform
-  const int nt = (a.prefix + (row_hi - 1) / a.G) / BN + 1;      // key tiles this workgroup walks
-  const int jw = wave_active ? wmax / BN + 1 : 0;               // key tiles this wave needs
+  const int nt = jt1 - jt0;                                     // key tiles this fragment walks
+  // key tiles of the fragment this wave needs (its rows see keys up to wmax)
+  const int jw = wave_active ? min(max(wmax / BN + 1 - jt0, 0), nt) : 0;
 
   // Q fragment: B operand of S^T, lane (n, kg) holds Q[row n][16 ks + 8 kg .. +7]
   bf16x8 qf[KS];
@@ -162,8 +186,8 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_attn_kernel(AttnArgs a) {
   // tile kt of K (or V) -> ring slot buf; rows past the end of the cache repeat the last valid row
   auto dma_tile = [&](const __bf16* head_base, const unsigned (&off)[LOADS], const unsigned (&cc)[LOADS],
                       int kt, u32x4* dst) {
-    const __bf16* base = head_base + static_cast<long long>(kt) * BN * row_stride;
-    const int lim = total - 1 - kt * BN;
+    const __bf16* base = head_base + static_cast<long long>(jt0 + kt) * BN * row_stride;
+    const int lim = total - 1 - (jt0 + kt) * BN;
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
       const unsigned o32 = (lim >= BN - 1) ? off[i]
@@ -186,7 +210,10 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_attn_kernel(AttnArgs a) {
   for (int db = 0; db < DB; ++db)
 #pragma unroll
     for (int e = 0; e < 16; ++e) o[db][e] = 0.0f;
-  float m = -INFINITY;   // exponent reference of the row (scaled by c_log2); >= running max - slack
+  // exponent reference of the row (scaled by c_log2), >= running max - slack.  A huge negative
+  // FINITE start value: a row that has not met a visible key yet (possible when a fragment starts
+  // beyond the row's last key) then yields p = exp2(-inf) = 0 and alpha = exp2(0) = 1, never NaN.
+  float m = kNoKeyYet;
   float l = 0.0f;        // running row sum of this lane's half of the keys
   const float c = a.c_log2;
 
@@ -284,8 +311,8 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_attn_kernel(AttnArgs a) {
     const int issued = (st >= 1) ? stage(st + 1) : 0;
     if (j < jw) {
       // register e of block mb is key  j*BN + 32 mb + 8 (e/4) + 4 kg + e%4  of query n
-      if (j * BN + BN - 1 > wmin) {
-        int rel = qpos - j * BN - 4 * kg;   // largest still-visible key offset (minus 4 kg)
+      if ((jt0 + j) * BN + BN - 1 > wmin) {
+        int rel = qpos - (jt0 + j) * BN - 4 * kg;   // largest still-visible key offset (minus 4 kg)
         // opaque to the optimiser: otherwise the 32 compares below become 32 loop-carried
         // counters that are kept up to date (and kept in registers) on every tile
         asm volatile("" : "+v"(rel));
@@ -340,6 +367,17 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_attn_kernel(AttnArgs a) {
   if (phase == 0) __syncthreads();   // both groups execute the same number of barriers
 
   // ---- epilogue: O / l, bf16, store -----------------------------------------------------------
+  if (partial != nullptr) {
+    // [wave][register][lane]: every store is 256 consecutive bytes per wave
+    float* p = partial + (wave * (DB * 16 + 2)) * 64 + lane;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) p[(db * 16 + e) * 64] = o[db][e];
+    p[(DB * 16) * 64] = m;
+    p[(DB * 16 + 1) * 64] = l;
+    return;
+  }
   const float lsum = l + other_half(l);
   if (wave_active && row_valid) {
     const float inv = 1.0f / lsum;
@@ -355,6 +393,171 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_attn_kernel(AttnArgs a) {
       }
   }
 }
+
+// One workgroup per unit, every unit whole.
+template <int D>
+__global__ __launch_bounds__(kThreads, 1) void chunk_attn_kernel(AttnArgs a) {
+  extern __shared__ u32x4 smem[];
+  // workgroup -> (kv head, row tile): longest row tiles first; with Hkv a multiple of 8 the
+  // heads are dealt to the 8 XCDs (workgroup ids go round-robin over XCDs) so that each
+  // XCD's L2 holds the K/V stream of its own heads only.
+  int g, qt;
+  {
+    const int bid = blockIdx.x;
+    if ((a.Hkv & 7) == 0) {
+      const int xcd = bid & 7, j = bid >> 3, hp = a.Hkv >> 3;
+      g = xcd + 8 * (j % hp);
+      qt = a.nq_tiles - 1 - j / hp;
+    } else {
+      g = bid % a.Hkv;
+      qt = a.nq_tiles - 1 - bid / a.Hkv;
+    }
+  }
+  attend<D>(a, smem, g, qt, 0, unit_steps(a, qt), nullptr);
+}
+
+// Key-split launch for chunks whose units do not fill the CUs evenly: one workgroup per CU, each
+// takes an equal run of key-tile steps, i.e. the tail of one unit, whole units, the head of another.
+// Whole units are finished here; the pieces of split units go to scratch.
+template <int D>
+__global__ __launch_bounds__(kThreads, 1) void chunk_attn_sk_kernel(AttnArgs a) {
+  extern __shared__ u32x4 smem[];
+  const int x = blockIdx.x % a.sk_groups, i = blockIdx.x / a.sk_groups;
+  const int hp = a.Hkv / a.sk_groups;
+  const long long total = sk_group_steps(a);
+  long long s = sk_cut(total, i, a.sk_wgs);
+  const long long s_end = sk_cut(total, i + 1, a.sk_wgs);
+  // locate the unit that holds step s
+  int qt = a.nq_tiles - 1;
+  long long base = 0;                       // first step of row-tile block qt
+  while (qt > 0 && s >= base + static_cast<long long>(hp) * unit_steps(a, qt)) {
+    base += static_cast<long long>(hp) * unit_steps(a, qt);
+    --qt;
+  }
+  bool first = true;
+  while (s < s_end) {
+    int n = unit_steps(a, qt);
+    if (s >= base + static_cast<long long>(hp) * n) {   // next row-tile block
+      base += static_cast<long long>(hp) * n;
+      --qt;
+      n = unit_steps(a, qt);
+    }
+    const int u = static_cast<int>((s - base) / n);     // unit inside the block = head index
+    const int off = static_cast<int>((s - base) - static_cast<long long>(u) * n);
+    const int len = static_cast<int>(min(static_cast<long long>(n - off), s_end - s));
+    const bool whole = off == 0 && len == n;
+    float* partial = whole ? nullptr
+                           : a.scratch + static_cast<long long>(2 * blockIdx.x + (first ? 0 : 1)) * kPartialFloats(D);
+    attend<D>(a, smem, x + a.sk_groups * u, qt, off, off + len, partial);
+    __syncthreads();   // the next fragment's prologue rewrites the LDS rings
+    s += len;
+    first = false;
+  }
+}
+
+// Merges the pieces of every unit that the key-split launch cut: one single-wave workgroup per
+// (unit, 32-row slice), lanes as in the main kernel.
+template <int D>
+__global__ __launch_bounds__(64) void chunk_attn_fixup_kernel(AttnArgs a) {
+  constexpr int DB = D / 32;
+  const int unit = blockIdx.x / kWaves, wave = blockIdx.x % kWaves;
+  const int x = unit % a.sk_groups, j = unit / a.sk_groups;
+  const int hp = a.Hkv / a.sk_groups;
+  const int qt = a.nq_tiles - 1 - j / hp, u = j % hp;
+  const int g = x + a.sk_groups * u;
+  const long long total = sk_group_steps(a);
+  long long start = 0;
+  for (int t = a.nq_tiles - 1; t > qt; --t) start += static_cast<long long>(hp) * unit_steps(a, t);
+  const int n = unit_steps(a, qt);
+  start += static_cast<long long>(u) * n;
+  const long long end = start + n;
+  // workgroups of the group that hold the first and the last step of this unit
+  auto holder = [&](long long step) {
+    int w = static_cast<int>(step * a.sk_wgs / total);
+    while (w + 1 < a.sk_wgs && sk_cut(total, w + 1, a.sk_wgs) <= step) ++w;
+    while (w > 0 && sk_cut(total, w, a.sk_wgs) > step) --w;
+    return w;
+  };
+  const int w_lo = holder(start), w_hi = holder(end - 1);
+  if (w_lo == w_hi) return;   // the unit was finished by one workgroup
+
+  const int lane = threadIdx.x;
+  const int nn = lane & 31, kg = lane >> 5;
+  const int VR = a.chunk * a.G;
+  const int row_lo = qt * a.rows_per_wg;
+  const int row_hi = min(row_lo + a.rows_per_wg, VR);
+  const int vr = row_lo + wave * 32 + nn;
+  if (row_lo + wave * 32 >= row_hi) return;   // slice beyond the tile (wave-uniform)
+
+  float o[DB][16];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) o[db][e] = 0.0f;
+  float m = kNoKeyYet, l = 0.0f;
+  for (int w = w_lo; w <= w_hi; ++w) {
+    const long long wb = sk_cut(total, w, a.sk_wgs), we = sk_cut(total, w + 1, a.sk_wgs);
+    if (max(wb, start) >= min(we, end)) continue;            // workgroup without steps in this unit
+    // a workgroup's first piece sits in its slot 0, a later (necessarily last) one in slot 1
+    const int slot = 2 * (x + a.sk_groups * w) + ((w == w_lo && wb < start) ? 1 : 0);
+    const float* p = a.scratch + static_cast<long long>(slot) * kPartialFloats(D) + (wave * (DB * 16 + 2)) * 64 + lane;
+    const float pm = p[(DB * 16) * 64], pl = p[(DB * 16 + 1) * 64];
+    const float mnew = fmaxf(m, pm);
+    const float wa = __builtin_amdgcn_exp2f(m - mnew), wbq = __builtin_amdgcn_exp2f(pm - mnew);
+    l = l * wa + pl * wbq;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[db][e] = o[db][e] * wa + p[(db * 16 + e) * 64] * wbq;
+    m = mnew;
+  }
+  const float lsum = l + other_half(l);
+  if (vr < row_hi) {
+    const int r = vr / a.G;
+    const int h = g * a.G + (vr - r * a.G);
+    const float inv = 1.0f / lsum;
+    __bf16* orow = a.out + (static_cast<long long>(r) * a.H + h) * D;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        bf16x4 w4;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) w4[t] = static_cast<__bf16>(o[db][4 * r4 + t] * inv);
+        *reinterpret_cast<bf16x4*>(orow + 32 * db + 8 * r4 + 4 * kg) = w4;
+      }
+  }
+}
+
+namespace {
+
+// Per-device scratch of the key-split path: two partial-result slots per workgroup, allocated on
+// first use and kept until the process ends.
+constexpr int kMaxDevices = 16;
+float* g_scratch[kMaxDevices] = {};
+int g_cus[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+float* device_scratch(int* cus_out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_cus[dev] == 0) {
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 8) cus = -1;
+    g_cus[dev] = cus;
+    if (cus > 0) {
+      const size_t bytes = static_cast<size_t>(2) * cus * kPartialFloats(128) * sizeof(float);
+      void* p = nullptr;
+      if (hipMalloc(&p, bytes) == hipSuccess) g_scratch[dev] = static_cast<float*>(p);
+      else (void)hipGetLastError();   // leave no sticky error behind; the plain launch needs no scratch
+    }
+  }
+  *cus_out = g_cus[dev];
+  return g_scratch[dev];
+}
+
+}  // namespace
 
 int launch_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
                       int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_kv_heads, int head_dim,
@@ -379,10 +582,44 @@ int launch_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
   a.nq_tiles = static_cast<int>(tiles);
   a.rows_per_wg = static_cast<int>(32 * slices_per_tile);
   a.c_log2 = scale * 1.4426950408889634f;
-  const int64_t grid = tiles * n_kv_heads;
-  if (grid > 0x7FFFFFFF) return KVRA_EUNSUPPORTED;
-  const dim3 g3(static_cast<unsigned>(grid)), b3(kThreads);
+  a.scratch = nullptr;
+  a.sk_groups = 1;
+  a.sk_wgs = 0;
+  const int64_t units = tiles * n_kv_heads;
+  if (units > 0x7FFFFFFF) return KVRA_EUNSUPPORTED;
   const unsigned smem = 2u * kStages * kBN * static_cast<unsigned>(head_dim) * 2u;   // K ring + V ring
+  const dim3 b3(kThreads);
+
+  // Key-split launch when whole units would leave more than a fifth of the CU-rounds empty (e.g. 160,
+  // 192 or 320 units on 256 CUs; a few long units of a short chunk behind a long prefix), as long as
+  // every workgroup still gets at least kMinSteps key tiles and the step bookkeeping stays short.
+  constexpr int kMinSteps = 16;
+  int cus = 0;
+  float* scratch = tiles <= 256 ? device_scratch(&cus) : nullptr;
+  if (scratch != nullptr && cus > 0) {
+    const int64_t rounds = (units + cus - 1) / cus;
+    const bool uneven = units * 5 < rounds * cus * 4;
+    const int groups = (n_kv_heads % 8 == 0 && cus % 8 == 0) ? 8 : 1;
+    int64_t steps = 0;   // key tiles over all units (same formula as unit_steps on the device)
+    for (int64_t qt = 0; qt < tiles; ++qt) {
+      const int64_t row_hi = std::min<int64_t>((qt + 1) * a.rows_per_wg, vrows);
+      steps += (prefix_len + (row_hi - 1) / G) / kBN + 1;
+    }
+    steps *= n_kv_heads;
+    const int64_t wgs = std::min<int64_t>(cus, steps / kMinSteps) / groups * groups;
+    if (uneven && wgs >= 2 * groups) {
+      a.scratch = scratch;
+      a.sk_groups = groups;
+      a.sk_wgs = static_cast<int>(wgs / groups);
+      const dim3 g_main(static_cast<unsigned>(wgs)), g_fix(static_cast<unsigned>(units * kWaves));
+      int rc = head_dim == 128 ? launch_kernel(chunk_attn_sk_kernel<128>, g_main, b3, a, stream, smem)
+                               : launch_kernel(chunk_attn_sk_kernel<64>, g_main, b3, a, stream, smem);
+      if (rc != KVRA_OK) return rc;
+      return head_dim == 128 ? launch_kernel(chunk_attn_fixup_kernel<128>, g_fix, dim3(64), a, stream)
+                             : launch_kernel(chunk_attn_fixup_kernel<64>, g_fix, dim3(64), a, stream);
+    }
+  }
+  const dim3 g3(static_cast<unsigned>(units));
   if (head_dim == 128) return launch_kernel(chunk_attn_kernel<128>, g3, b3, a, stream, smem);
   return launch_kernel(chunk_attn_kernel<64>, g3, b3, a, stream, smem);
 }

@@ -235,3 +235,17 @@ def test_long_context_sampled_rows():
     print(f"long context: {len(rows)} rows: max-abs {mx:.3e} mean-abs {mean:.3e}")
     np.testing.assert_array_equal(res["v_cache"], v)
     assert np.all(np.isfinite(_f64(res["out"])))
+
+
+@pytest.mark.parametrize("H,Hkv,d,prefix,c", [(32, 32, 128, 20000, 8), (8, 8, 64, 12345, 1), (32, 8, 128, 3000, 1280),
+                                               (71, 1, 64, 9000, 300)])
+def test_key_split_launch_shapes(H, Hkv, d, prefix, c):
+    """Shapes whose few (or unevenly many) work units make the library cut them along the keys:
+    a short chunk behind a long prefix (down to a single token), and unit counts between one and
+    two rounds of CUs.  Every row of the chunk is checked."""
+    C = prefix + c
+    q, k, v, scale, res = _run(32, 1, C, H, Hkv, d, [0, prefix, C])
+    rows = list(range(prefix, C))
+    want = orc.attention_rows(_f64(q), _f64(k), _f64(v), rows, scale, rope_base=synth.ROPE_BASE)
+    mx, mean = _check_out(res["out"][rows], want, f"key-split {H}/{Hkv} d{d} prefix {prefix} c {c}")
+    print(f"key-split {H}/{Hkv} d{d} prefix {prefix} c {c}: max-abs {mx:.3e} mean-abs {mean:.3e}")
