@@ -17,9 +17,11 @@
  *     reads key/value head h / (n_q_heads / n_kv_heads).
  *   - The only state the library keeps is one scratch buffer per device (about 70 MB, hipMalloc'ed
  *     by the first kvra_chunk_attn call on that device, kept until the process ends).  It holds
- *     the partial results of key-split launches; two kvra_chunk_attn calls (kvra_layer_chunk
- *     included) that overlap in time on one device, from different streams, would share it and
- *     are not supported.  If the allocation fails the call runs without key-splitting.
+ *     the partial results of key-split launches, which kvra_chunk_attn takes when a call has fewer
+ *     (kv head, 256-row tile) units than the device has CUs - a short chunk behind a long prefix.
+ *     Two such calls (kvra_layer_chunk included) that overlap in time on one device, from
+ *     different streams, would share it and are not supported.  If the allocation fails the call
+ *     runs without key-splitting.
  */
 #ifndef KVRA_H
 #define KVRA_H

@@ -22,10 +22,11 @@
 //
 // Launch shapes.  Normally one workgroup per unit (kv head, 256-row tile), every unit whole.  When
 // the units would fill the CUs unevenly (160 or 320 units on 256 CUs; a handful of very long units
-// for a short chunk behind a long prefix) the launch is key-split instead: one workgroup per CU
-// takes an equal run of the key-tile steps of all units laid end to end, whole units are finished
-// in place, and the pieces of the units that a cut falls into go through a per-device scratch
-// buffer to a small fix-up kernel that merges them (the usual log-sum-exp merge).
+// for a short chunk behind a long prefix), the units beyond the last full round of CUs are cut
+// into S equal key segments each, one workgroup per segment, issued segment by segment so that
+// the row tiles of a head still sweep the same keys at the same time (which is what lets them
+// share the K/V stream in L2).  The un-normalised pieces go through a per-device scratch buffer to
+// a small fix-up kernel that merges them (the usual log-sum-exp merge).
 #include "kvra_internal.h"
 
 #include <algorithm>
@@ -64,30 +65,30 @@ struct AttnArgs {
   int nq_tiles;      // row tiles per kv head
   int rows_per_wg;   // virtual rows per workgroup: 32 * (active waves), <= 256
   float c_log2;      // scale * log2(e): softmax runs in base 2
-  // key-split ("stream-K") launches only
-  float* scratch;    // partial results, 2 slots per workgroup
-  int sk_groups;     // workgroup / unit groups (8 = one per XCD when Hkv % 8 == 0, else 1)
-  int sk_wgs;        // workgroups per group
+  // key-split launches only
+  float* scratch;    // partial results, one slot per (split unit, key segment)
+  int n_whole;       // workgroups [0, n_whole) take whole units
+  int n_split;       // the next n_split units are cut into `segments` key segments each
+  int segments;
 };
 
-// Work units of a launch.  Unit = (kv head g, row tile qt); the units of group x, in order
-// j = 0, 1, ..: g = x + groups * (j % hp), qt = nq_tiles - 1 - j / hp, hp = Hkv / groups heads per
-// group (longest row tiles first).  A unit walks unit_steps(qt) key tiles.
-__device__ __forceinline__ int unit_row_hi(const AttnArgs& a, int qt) {
-  return min((qt + 1) * a.rows_per_wg, a.chunk * a.G);   // exclusive, in virtual rows
+// Work units of a launch.  Unit index u -> (kv head g, row tile qt), longest row tiles first; with
+// Hkv a multiple of 8 the heads are dealt to the 8 XCDs (workgroup ids go round-robin over XCDs,
+// and a workgroup's unit index has its own id's low three bits) so that each XCD's L2 holds the
+// K/V stream of its own heads only.
+__device__ __forceinline__ void unit_of(const AttnArgs& a, int u, int* g, int* qt) {
+  if ((a.Hkv & 7) == 0) {
+    const int xcd = u & 7, j = u >> 3, hp = a.Hkv >> 3;
+    *g = xcd + 8 * (j % hp);
+    *qt = a.nq_tiles - 1 - j / hp;
+  } else {
+    *g = u % a.Hkv;
+    *qt = a.nq_tiles - 1 - u / a.Hkv;
+  }
 }
 __device__ __forceinline__ int unit_steps(const AttnArgs& a, int qt) {
-  return (a.prefix + (unit_row_hi(a, qt) - 1) / a.G) / kBN + 1;
-}
-// Key-split schedule: the key-tile steps of a group's units, laid end to end, are cut into sk_wgs
-// equal runs; workgroup i of the group takes steps [sk_cut(T, i), sk_cut(T, i + 1)).
-__device__ __forceinline__ long long sk_cut(long long total_steps, int i, int wgs) {
-  return total_steps * i / wgs;
-}
-__device__ __forceinline__ long long sk_group_steps(const AttnArgs& a) {
-  long long t = 0;
-  for (int qt = 0; qt < a.nq_tiles; ++qt) t += unit_steps(a, qt);
-  return t * (a.Hkv / a.sk_groups);
+  const int row_hi = min((qt + 1) * a.rows_per_wg, a.chunk * a.G);   // exclusive, in virtual rows
+  return (a.prefix + (row_hi - 1) / a.G) / kBN + 1;                  // key tiles the row tile walks
 }
 constexpr int kPartialFloats(int D) { return kWaves * (D / 32 * 16 + 2) * 64; }   // per scratch slot
 
@@ -394,93 +395,34 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, const int
   }
 }
 
-// One workgroup per unit, every unit whole.
+// One workgroup per whole unit, then one per key segment of the split units (segment-major).
 template <int D>
 __global__ __launch_bounds__(kThreads, 1) void chunk_attn_kernel(AttnArgs a) {
   extern __shared__ u32x4 smem[];
-  // workgroup -> (kv head, row tile): longest row tiles first; with Hkv a multiple of 8 the
-  // heads are dealt to the 8 XCDs (workgroup ids go round-robin over XCDs) so that each
-  // XCD's L2 holds the K/V stream of its own heads only.
+  const int bid = blockIdx.x;
   int g, qt;
-  {
-    const int bid = blockIdx.x;
-    if ((a.Hkv & 7) == 0) {
-      const int xcd = bid & 7, j = bid >> 3, hp = a.Hkv >> 3;
-      g = xcd + 8 * (j % hp);
-      qt = a.nq_tiles - 1 - j / hp;
-    } else {
-      g = bid % a.Hkv;
-      qt = a.nq_tiles - 1 - bid / a.Hkv;
-    }
+  if (bid < a.n_whole) {
+    unit_of(a, bid, &g, &qt);
+    attend<D>(a, smem, g, qt, 0, unit_steps(a, qt), nullptr);
+    return;
   }
-  attend<D>(a, smem, g, qt, 0, unit_steps(a, qt), nullptr);
+  const int f = bid - a.n_whole;
+  const int seg = f / a.n_split, ui = f - seg * a.n_split;
+  unit_of(a, a.n_whole + ui, &g, &qt);
+  const long long n = unit_steps(a, qt);
+  const int jt0 = static_cast<int>(n * seg / a.segments), jt1 = static_cast<int>(n * (seg + 1) / a.segments);
+  float* partial = a.scratch + static_cast<long long>(ui * a.segments + seg) * kPartialFloats(D);
+  attend<D>(a, smem, g, qt, jt0, jt1, partial);
 }
 
-// Key-split launch for chunks whose units do not fill the CUs evenly: one workgroup per CU, each
-// takes an equal run of key-tile steps, i.e. the tail of one unit, whole units, the head of another.
-// Whole units are finished here; the pieces of split units go to scratch.
-template <int D>
-__global__ __launch_bounds__(kThreads, 1) void chunk_attn_sk_kernel(AttnArgs a) {
-  extern __shared__ u32x4 smem[];
-  const int x = blockIdx.x % a.sk_groups, i = blockIdx.x / a.sk_groups;
-  const int hp = a.Hkv / a.sk_groups;
-  const long long total = sk_group_steps(a);
-  long long s = sk_cut(total, i, a.sk_wgs);
-  const long long s_end = sk_cut(total, i + 1, a.sk_wgs);
-  // locate the unit that holds step s
-  int qt = a.nq_tiles - 1;
-  long long base = 0;                       // first step of row-tile block qt
-  while (qt > 0 && s >= base + static_cast<long long>(hp) * unit_steps(a, qt)) {
-    base += static_cast<long long>(hp) * unit_steps(a, qt);
-    --qt;
-  }
-  bool first = true;
-  while (s < s_end) {
-    int n = unit_steps(a, qt);
-    if (s >= base + static_cast<long long>(hp) * n) {   // next row-tile block
-      base += static_cast<long long>(hp) * n;
-      --qt;
-      n = unit_steps(a, qt);
-    }
-    const int u = static_cast<int>((s - base) / n);     // unit inside the block = head index
-    const int off = static_cast<int>((s - base) - static_cast<long long>(u) * n);
-    const int len = static_cast<int>(min(static_cast<long long>(n - off), s_end - s));
-    const bool whole = off == 0 && len == n;
-    float* partial = whole ? nullptr
-                           : a.scratch + static_cast<long long>(2 * blockIdx.x + (first ? 0 : 1)) * kPartialFloats(D);
-    attend<D>(a, smem, x + a.sk_groups * u, qt, off, off + len, partial);
-    __syncthreads();   // the next fragment's prologue rewrites the LDS rings
-    s += len;
-    first = false;
-  }
-}
-
-// Merges the pieces of every unit that the key-split launch cut: one single-wave workgroup per
-// (unit, 32-row slice), lanes as in the main kernel.
+// Merges the key segments of every split unit: one single-wave workgroup per (unit, 32-row slice,
+// 32-wide block of d), lanes as in the main kernel.
 template <int D>
 __global__ __launch_bounds__(64) void chunk_attn_fixup_kernel(AttnArgs a) {
   constexpr int DB = D / 32;
-  const int unit = blockIdx.x / kWaves, wave = blockIdx.x % kWaves;
-  const int x = unit % a.sk_groups, j = unit / a.sk_groups;
-  const int hp = a.Hkv / a.sk_groups;
-  const int qt = a.nq_tiles - 1 - j / hp, u = j % hp;
-  const int g = x + a.sk_groups * u;
-  const long long total = sk_group_steps(a);
-  long long start = 0;
-  for (int t = a.nq_tiles - 1; t > qt; --t) start += static_cast<long long>(hp) * unit_steps(a, t);
-  const int n = unit_steps(a, qt);
-  start += static_cast<long long>(u) * n;
-  const long long end = start + n;
-  // workgroups of the group that hold the first and the last step of this unit
-  auto holder = [&](long long step) {
-    int w = static_cast<int>(step * a.sk_wgs / total);
-    while (w + 1 < a.sk_wgs && sk_cut(total, w + 1, a.sk_wgs) <= step) ++w;
-    while (w > 0 && sk_cut(total, w, a.sk_wgs) > step) --w;
-    return w;
-  };
-  const int w_lo = holder(start), w_hi = holder(end - 1);
-  if (w_lo == w_hi) return;   // the unit was finished by one workgroup
-
+  const int db = blockIdx.x % DB, wave = (blockIdx.x / DB) % kWaves, ui = blockIdx.x / (DB * kWaves);
+  int g, qt;
+  unit_of(a, a.n_whole + ui, &g, &qt);
   const int lane = threadIdx.x;
   const int nn = lane & 31, kg = lane >> 5;
   const int VR = a.chunk * a.G;
@@ -489,27 +431,22 @@ __global__ __launch_bounds__(64) void chunk_attn_fixup_kernel(AttnArgs a) {
   const int vr = row_lo + wave * 32 + nn;
   if (row_lo + wave * 32 >= row_hi) return;   // slice beyond the tile (wave-uniform)
 
-  float o[DB][16];
+  // exponent references first: the merged one is their maximum
+  const float* base = a.scratch + static_cast<long long>(ui * a.segments) * kPartialFloats(D) +
+                      (wave * (DB * 16 + 2)) * 64 + lane;
+  float m = kNoKeyYet;
+  for (int seg = 0; seg < a.segments; ++seg)
+    m = fmaxf(m, base[static_cast<long long>(seg) * kPartialFloats(D) + (DB * 16) * 64]);
+  float o[16];
 #pragma unroll
-  for (int db = 0; db < DB; ++db)
+  for (int e = 0; e < 16; ++e) o[e] = 0.0f;
+  float l = 0.0f;
+  for (int seg = 0; seg < a.segments; ++seg) {
+    const float* p = base + static_cast<long long>(seg) * kPartialFloats(D);
+    const float w = __builtin_amdgcn_exp2f(p[(DB * 16) * 64] - m);
+    l = fmaf(p[(DB * 16 + 1) * 64], w, l);
 #pragma unroll
-    for (int e = 0; e < 16; ++e) o[db][e] = 0.0f;
-  float m = kNoKeyYet, l = 0.0f;
-  for (int w = w_lo; w <= w_hi; ++w) {
-    const long long wb = sk_cut(total, w, a.sk_wgs), we = sk_cut(total, w + 1, a.sk_wgs);
-    if (max(wb, start) >= min(we, end)) continue;            // workgroup without steps in this unit
-    // a workgroup's first piece sits in its slot 0, a later (necessarily last) one in slot 1
-    const int slot = 2 * (x + a.sk_groups * w) + ((w == w_lo && wb < start) ? 1 : 0);
-    const float* p = a.scratch + static_cast<long long>(slot) * kPartialFloats(D) + (wave * (DB * 16 + 2)) * 64 + lane;
-    const float pm = p[(DB * 16) * 64], pl = p[(DB * 16 + 1) * 64];
-    const float mnew = fmaxf(m, pm);
-    const float wa = __builtin_amdgcn_exp2f(m - mnew), wbq = __builtin_amdgcn_exp2f(pm - mnew);
-    l = l * wa + pl * wbq;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) o[db][e] = o[db][e] * wa + p[(db * 16 + e) * 64] * wbq;
-    m = mnew;
+    for (int e = 0; e < 16; ++e) o[e] = fmaf(p[(db * 16 + e) * 64], w, o[e]);
   }
   const float lsum = l + other_half(l);
   if (vr < row_hi) {
@@ -518,21 +455,19 @@ __global__ __launch_bounds__(64) void chunk_attn_fixup_kernel(AttnArgs a) {
     const float inv = 1.0f / lsum;
     __bf16* orow = a.out + (static_cast<long long>(r) * a.H + h) * D;
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+    for (int r4 = 0; r4 < 4; ++r4) {
+      bf16x4 w4;
 #pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        bf16x4 w4;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) w4[t] = static_cast<__bf16>(o[db][4 * r4 + t] * inv);
-        *reinterpret_cast<bf16x4*>(orow + 32 * db + 8 * r4 + 4 * kg) = w4;
-      }
+      for (int t = 0; t < 4; ++t) w4[t] = static_cast<__bf16>(o[4 * r4 + t] * inv);
+      *reinterpret_cast<bf16x4*>(orow + 32 * db + 8 * r4 + 4 * kg) = w4;
+    }
   }
 }
 
 namespace {
 
-// Per-device scratch of the key-split path: two partial-result slots per workgroup, allocated on
-// first use and kept until the process ends.
+// Per-device scratch of the key-split path: two partial-result slots per CU, allocated on first
+// use and kept until the process ends.
 constexpr int kMaxDevices = 16;
 float* g_scratch[kMaxDevices] = {};
 int g_cus[kMaxDevices] = {};
@@ -583,37 +518,49 @@ int launch_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
   a.rows_per_wg = static_cast<int>(32 * slices_per_tile);
   a.c_log2 = scale * 1.4426950408889634f;
   a.scratch = nullptr;
-  a.sk_groups = 1;
-  a.sk_wgs = 0;
+  a.n_whole = static_cast<int>(tiles * n_kv_heads);
+  a.n_split = 0;
+  a.segments = 1;
   const int64_t units = tiles * n_kv_heads;
   if (units > 0x7FFFFFFF) return KVRA_EUNSUPPORTED;
   const unsigned smem = 2u * kStages * kBN * static_cast<unsigned>(head_dim) * 2u;   // K ring + V ring
   const dim3 b3(kThreads);
 
-  // Key-split launch when whole units would leave more than a fifth of the CU-rounds empty (e.g. 160,
-  // 192 or 320 units on 256 CUs; a few long units of a short chunk behind a long prefix), as long as
-  // every workgroup still gets at least kMinSteps key tiles and the step bookkeeping stays short.
-  constexpr int kMinSteps = 16;
+  // Key-split launch, for launches with fewer units than CUs: every unit is cut into S key
+  // segments.  Time in units of a whole row tile: 1 without the split, t(S) = ceil(units * S / CUs) / S
+  // with it.  Feasible S: one scratch slot per piece (2 per CU) and at least kMinSteps key tiles per
+  // piece.  Taken: the smallest S within a tenth of the best t, if that is at most 0.5.  (Filling the
+  // chip from 60-75 % to 100 % does not pay on this power-managed part: the busy CUs clock higher
+  // when the others idle - measured +0..5 % after the cost of the extra traffic and the fix-up.)
+  constexpr int kMinSteps = 16, kMaxSegments = 16;
   int cus = 0;
-  float* scratch = tiles <= 256 ? device_scratch(&cus) : nullptr;
+  float* scratch = device_scratch(&cus);
   if (scratch != nullptr && cus > 0) {
-    const int64_t rounds = (units + cus - 1) / cus;
-    const bool uneven = units * 5 < rounds * cus * 4;
-    const int groups = (n_kv_heads % 8 == 0 && cus % 8 == 0) ? 8 : 1;
-    int64_t steps = 0;   // key tiles over all units (same formula as unit_steps on the device)
-    for (int64_t qt = 0; qt < tiles; ++qt) {
-      const int64_t row_hi = std::min<int64_t>((qt + 1) * a.rows_per_wg, vrows);
-      steps += (prefix_len + (row_hi - 1) / G) / kBN + 1;
+    const int64_t rest = units % cus;
+    // shortest split unit = the last row tile
+    const int64_t last_rows = std::min<int64_t>(a.rows_per_wg, vrows);
+    const int64_t min_steps = (prefix_len + (last_rows - 1) / G) / kBN + 1;
+    int best = 1;
+    if (rest > 0 && units < cus) {
+      double t[kMaxSegments + 1], t_min = 1.0;
+      int s_max = 1;
+      for (int S = 2; S <= kMaxSegments; ++S) {
+        if (rest * S > 2 * static_cast<int64_t>(cus) || min_steps / S < kMinSteps) break;
+        t[S] = static_cast<double>((rest * S + cus - 1) / cus) / S;
+        t_min = std::min(t_min, t[S]);
+        s_max = S;
+      }
+      for (int S = 2; S <= s_max; ++S)
+        if (t[S] <= 0.5 && t[S] <= 1.1 * t_min) { best = S; break; }
     }
-    steps *= n_kv_heads;
-    const int64_t wgs = std::min<int64_t>(cus, steps / kMinSteps) / groups * groups;
-    if (uneven && wgs >= 2 * groups) {
+    if (best > 1) {
       a.scratch = scratch;
-      a.sk_groups = groups;
-      a.sk_wgs = static_cast<int>(wgs / groups);
-      const dim3 g_main(static_cast<unsigned>(wgs)), g_fix(static_cast<unsigned>(units * kWaves));
-      int rc = head_dim == 128 ? launch_kernel(chunk_attn_sk_kernel<128>, g_main, b3, a, stream, smem)
-                               : launch_kernel(chunk_attn_sk_kernel<64>, g_main, b3, a, stream, smem);
+      a.n_whole = static_cast<int>(units - rest);
+      a.n_split = static_cast<int>(rest);
+      a.segments = best;
+      const dim3 g_main(static_cast<unsigned>(a.n_whole + rest * best)), g_fix(static_cast<unsigned>(rest * kWaves * (head_dim / 32)));
+      int rc = head_dim == 128 ? launch_kernel(chunk_attn_kernel<128>, g_main, b3, a, stream, smem)
+                               : launch_kernel(chunk_attn_kernel<64>, g_main, b3, a, stream, smem);
       if (rc != KVRA_OK) return rc;
       return head_dim == 128 ? launch_kernel(chunk_attn_fixup_kernel<128>, g_fix, dim3(64), a, stream)
                              : launch_kernel(chunk_attn_fixup_kernel<64>, g_fix, dim3(64), a, stream);
