@@ -227,3 +227,60 @@ def test_interpolate_and_table_predict_equal_the_oracle():
         kvra.kvra_interpolate(1024, 64, 4096, [0, 4096, 4096], 8192, [0, 2048, 8192])   # not rising
     with pytest.raises(kvra.KvraError):
         kvra.kvra_interpolate(1000, 64, 4096, [0, 2048, 4096], 8192, [0, 2048, 8192])   # off the grid
+
+
+# ---------------------------------------------------------------- decoder layer: checks that need no GPU
+def _layer(**over):
+    f = dict(hidden=4096, ffn=11008, n_q_heads=32, n_kv_heads=32, head_dim=128, rms_eps=1e-6, rope_base=10000.0,
+             scale=128 ** -0.5, norm1=256, wqkv=256, wo=256, norm2=256, w_gate=256, w_up=256, w_down=256)
+    f.update(over)
+    return kvra.make_layer(**f)
+
+
+def test_layer_workspace_size_and_checks():
+    L = _layer()
+    c = 1000
+    # h, q, k, v, attention output, x2 [c, 4096] and the MLP activation [c, 11008], bf16, 256-byte aligned
+    want = 6 * c * 4096 * 2 + c * 11008 * 2
+    got = kvra.kvra_layer_workspace_bytes(L, c)
+    assert want <= got <= want + 7 * 256
+    gqa = _layer(n_kv_heads=8)
+    assert kvra.kvra_layer_workspace_bytes(gqa, c) < got
+    for bad in (_layer(hidden=4100), _layer(ffn=11000), _layer(head_dim=96), _layer(n_kv_heads=5),
+                _layer(scale=0.0), _layer(rms_eps=-1.0), _layer(wo=None), _layer(hidden=16384)):
+        with pytest.raises(kvra.KvraError):
+            kvra.kvra_layer_workspace_bytes(bad, c)
+    with pytest.raises(kvra.KvraError):
+        kvra.kvra_layer_workspace_bytes(L, 0)
+
+
+def test_layer_and_linear_reject_bad_arguments_before_any_launch():
+    L = _layer()
+    p = 256   # fake, never dereferenced: every call below is refused by the argument checks
+    nbytes = kvra.kvra_layer_workspace_bytes(L, 64)
+    with pytest.raises(kvra.KvraError) as e:
+        kvra.kvra_layer_chunk(L, p, p, p, p, 0, 64, 64, p, nbytes - 1)        # workspace too small
+    assert e.value.code == kvra.KVRA_EINVAL
+    with pytest.raises(kvra.KvraError):
+        kvra.kvra_layer_chunk(L, p, p, p, p, 0, 64, 64, p + 8, nbytes)        # workspace misaligned
+    with pytest.raises(kvra.KvraError) as e:
+        kvra.kvra_layer_chunk(L, p, p, p, p, 10, 64, 64, p, nbytes)           # past the cache capacity
+    assert e.value.code == kvra.KVRA_ERANGE
+    with pytest.raises(kvra.KvraError):
+        kvra.kvra_layer_chunk(L, None, p, p, p, 0, 64, 64, p, nbytes)
+    with pytest.raises(kvra.KvraError) as e:
+        kvra.kvra_linear(p, p, None, None, p, 8, 100, 64)                     # n not a multiple of 32
+    assert e.value.code == kvra.KVRA_EUNSUPPORTED
+    with pytest.raises(kvra.KvraError):
+        kvra.kvra_linear(p, p, None, None, p, 8, 64, 100)                     # k not a multiple of 64
+    with pytest.raises(kvra.KvraError) as e:
+        kvra.kvra_linear(p, p, p, p, p, 8, 64, 64)                            # gate/up together with residual
+    assert e.value.code == kvra.KVRA_EINVAL
+    with pytest.raises(kvra.KvraError):
+        kvra.kvra_linear(p, p, None, None, p, 1 << 20, 64, 4096)              # activation matrix beyond 4 GiB
+    with pytest.raises(kvra.KvraError):
+        kvra.kvra_qkv_proj(p, p, p, p, p, 8, 32, 5, 128, 4096)                # heads not divisible
+    with pytest.raises(kvra.KvraError):
+        kvra.kvra_rms_norm(p, p, p, 4, 100, 1e-6)                             # hidden not a multiple of 8
+    with pytest.raises(kvra.KvraError):
+        kvra.kvra_rms_norm(p, None, p, 4, 64, 1e-6)
