@@ -234,8 +234,8 @@ def layer_bench(args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the equal-split comparison runs")
     ap.add_argument("--workload", default=WORKLOAD,
@@ -274,7 +274,9 @@ def main():
     q_master, k_in, v_in = dev(qb), dev(kb), dev(vb)
     del qb, kb, vb
     n_buf = min(args.steps + args.warmup, 24)
-    q_work = [q_master.clone() for _ in range(n_buf)]      # Q is rotated in place: fresh copy per step
+    # Q is rotated in place, so steps take turns on n_buf copies; a copy that comes round again is
+    # rotated once more (same work; a rotation keeps the magnitudes, so the softmax load is unchanged)
+    q_work = [q_master.clone() for _ in range(n_buf)]
     k_cache = torch.zeros((C, Hkv, d), dtype=torch.bfloat16, device="cuda")
     v_cache = torch.zeros((C, Hkv, d), dtype=torch.bfloat16, device="cuda")
     out = torch.empty((C, H, d), dtype=torch.bfloat16, device="cuda")

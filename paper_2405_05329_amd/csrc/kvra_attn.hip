@@ -20,13 +20,12 @@
 // barrier after each block.  The second group starts one barrier late, so while one group keeps
 // the matrix pipe busy its SIMD partner does exp2/max/sum on the vector ALU ("ping-pong").
 //
-// Launch shapes.  Normally one workgroup per unit (kv head, 256-row tile), every unit whole.  When
-// the units would fill the CUs unevenly (160 or 320 units on 256 CUs; a handful of very long units
-// for a short chunk behind a long prefix), the units beyond the last full round of CUs are cut
-// into S equal key segments each, one workgroup per segment, issued segment by segment so that
-// the row tiles of a head still sweep the same keys at the same time (which is what lets them
-// share the K/V stream in L2).  The un-normalised pieces go through a per-device scratch buffer to
-// a small fix-up kernel that merges them (the usual log-sum-exp merge).
+// Launch shapes.  Normally one workgroup per unit (kv head, 256-row tile), every unit whole.  A
+// launch with fewer units than CUs (a short chunk behind a long prefix) cuts every unit into S
+// equal key segments instead, one workgroup per segment, issued segment by segment so that the row
+// tiles of a head still sweep the same keys at the same time (which is what lets them share the
+// K/V stream in L2).  The un-normalised pieces go through a per-device scratch buffer to a small
+// fix-up kernel that merges them (the usual log-sum-exp merge).
 #include "kvra_internal.h"
 
 #include <algorithm>
