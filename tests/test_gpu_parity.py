@@ -249,3 +249,52 @@ def test_key_split_launch_shapes(H, Hkv, d, prefix, c):
     want = orc.attention_rows(_f64(q), _f64(k), _f64(v), rows, scale, rope_base=synth.ROPE_BASE)
     mx, mean = _check_out(res["out"][rows], want, f"key-split {H}/{Hkv} d{d} prefix {prefix} c {c}")
     print(f"key-split {H}/{Hkv} d{d} prefix {prefix} c {c}: max-abs {mx:.3e} mean-abs {mean:.3e}")
+
+
+def _random_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        d = int(rng.choice([64, 128]))
+        Hkv = int(rng.choice([1, 2, 3, 8]))
+        G = int(rng.choice([1, 2, 3, 5, 8]))
+        p = int(rng.integers(1, 4))
+        C = int(rng.integers(p, 700))
+        cuts = sorted(int(x) for x in rng.choice(np.arange(1, C), size=p - 1, replace=False)) if p > 1 else []
+        cases.append((Hkv * G, Hkv, d, [0] + cuts + [C]))
+    return cases
+
+
+@pytest.mark.parametrize("H,Hkv,d,bounds", _random_cases(24, 2024))
+def test_random_shapes_full_check(H, Hkv, d, bounds):
+    """Seeded random head counts, group sizes, context lengths and partitions (chunks of any length,
+    boundaries off every tile grid), every output element against the oracle."""
+    C = bounds[-1]
+    q, k, v, scale, res = _run(33, 4, C, H, Hkv, d, bounds)
+    want = orc.causal_attention(_f64(q), _f64(k), _f64(v), scale, rope_base=synth.ROPE_BASE)
+    _check_out(res["out"], want, f"random {H}/{Hkv} d{d} {bounds}")
+    np.testing.assert_array_equal(res["v_cache"], v)
+
+
+def _random_split_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        d = int(rng.choice([64, 128]))
+        Hkv = int(rng.choice([1, 2, 4, 8]))
+        G = int(rng.choice([1, 2, 4, 7]))
+        prefix = int(rng.integers(2100, 9000))
+        c = int(rng.integers(1, 400))
+        cases.append((Hkv * G, Hkv, d, prefix, c))
+    return cases
+
+
+@pytest.mark.parametrize("H,Hkv,d,prefix,c", _random_split_cases(12, 77))
+def test_random_short_chunks_behind_long_prefixes(H, Hkv, d, prefix, c):
+    """Seeded random shapes in the range where launches are cut along the keys (few units, hundreds
+    of key tiles), every row of the chunk against the oracle."""
+    C = prefix + c
+    q, k, v, scale, res = _run(34, 5, C, H, Hkv, d, [0, prefix, C])
+    rows = list(range(prefix, C))
+    want = orc.attention_rows(_f64(q), _f64(k), _f64(v), rows, scale, rope_base=synth.ROPE_BASE)
+    _check_out(res["out"][rows], want, f"random short chunk {H}/{Hkv} d{d} prefix {prefix} c {c}")
