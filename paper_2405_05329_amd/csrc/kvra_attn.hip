@@ -48,7 +48,7 @@ constexpr int kWaves = 8;              // waves per workgroup
 constexpr int kThreads = 64 * kWaves;
 constexpr int kBN = 64;                // keys per tile
 constexpr int kStages = 3;             // LDS ring depth for K and for V tiles
-constexpr float kRescaleSlack = 8.0f;  // exponent headroom (log2) before the running max is moved
+constexpr float kSumLimit = 1048576.0f; // partial row sum (32 weights) beyond which the reference is moved
 constexpr float kNoKeyYet = -1e30f;    // exponent reference of a row before its first visible key
 
 struct AttnArgs {
@@ -210,7 +210,8 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, const int
   for (int db = 0; db < DB; ++db)
 #pragma unroll
     for (int e = 0; e < 16; ++e) o[db][e] = 0.0f;
-  // exponent reference of the row (scaled by c_log2), >= running max - slack.  A huge negative
+  // exponent reference of the row (scaled by c_log2); trails the running max by a bounded amount
+  // (see kSumLimit).  A huge negative
   // FINITE start value: a row that has not met a visible key yet (possible when a fragment starts
   // beyond the row's last key) then yields p = exp2(-inf) = 0 and alpha = exp2(0) = 1, never NaN.
   float m = kNoKeyYet;
@@ -323,15 +324,39 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, const int
             if (32 * mb + 8 * (e / 4) + (e % 4) > rel) s[mb][e] = -INFINITY;
       }
       // ---- online softmax (base 2) with a lazily moved exponent reference -------------------
-      float tmax = s[0][0];
+      // weights of this tile against the current reference: p = exp2(s c - m), rounded to bf16 in
+      // pairs; the row sum adds up the rounded values (v_dot2 with ones), i.e. exactly the weights
+      // the P.V product uses.  Returns this lane's part of the row sum.
+      auto weights = [&]() __attribute__((always_inline)) -> float {
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
+        float sum0 = 0.0f, sum1 = 0.0f;
 #pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
+        for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) tmax = fmaxf(tmax, s[mb][e]);
-      tmax = fmaxf(tmax, other_half(tmax)) * c;
-      // p = exp2(s c - m) stays <= 2^slack as long as the tile max is within the slack of m;
-      // only when some row of the wave outgrows it are m, l and O re-based (wave-uniform branch)
-      if (__builtin_amdgcn_ballot_w64(tmax > m + kRescaleSlack) != 0) {
+          for (int e = 0; e < 16; e += 2) {
+            const float p0 = __builtin_amdgcn_exp2f(fmaf(s[mb][e], c, -m));
+            const float p1 = __builtin_amdgcn_exp2f(fmaf(s[mb][e + 1], c, -m));
+            const bf16x2 pp = {static_cast<__bf16>(p0), static_cast<__bf16>(p1)};
+            if ((e / 2) % 2) sum1 = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, sum1, false);
+            else sum0 = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, sum0, false);
+            pf[mb][e / 8][e % 8] = pp[0];
+            pf[mb][e / 8][e % 8 + 1] = pp[1];
+          }
+        return sum0 + sum1;
+      };
+      // Optimistic pass: no row maximum is formed.  As long as the scores stay within reach of m the
+      // weights are modest; a lane whose partial sum gets out of hand (or is inf: a row's first
+      // visible keys, m = kNoKeyYet) sends the whole wave through the exact path: row maximum,
+      // m, l and O re-based to it, weights formed again.
+      float psum = weights();
+      if (__builtin_amdgcn_ballot_w64(!(psum < kSumLimit)) != 0) {
+        float tmax = s[0][0];
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) tmax = fmaxf(tmax, s[mb][e]);
+        tmax = fmaxf(tmax, other_half(tmax)) * c;
         const float mnew = fmaxf(m, tmax);
         const float alpha = __builtin_amdgcn_exp2f(m - mnew);
         l *= alpha;
@@ -340,16 +365,8 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, const int
         for (int db = 0; db < DB; ++db)
 #pragma unroll
           for (int e = 0; e < 16; ++e) o[db][e] *= alpha;
+        psum = weights();
       }
-      float psum = 0.0f;
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const float p = __builtin_amdgcn_exp2f(fmaf(s[mb][e], c, -m));
-          psum += p;
-          pf[mb][e / 8][e % 8] = static_cast<__bf16>(p);
-        }
       l += psum;
     }
     // everything issued before this block (tiles K(st+1), V(st)) must have landed before the barrier

@@ -298,3 +298,27 @@ def test_random_short_chunks_behind_long_prefixes(H, Hkv, d, prefix, c):
     rows = list(range(prefix, C))
     want = orc.attention_rows(_f64(q), _f64(k), _f64(v), rows, scale, rope_base=synth.ROPE_BASE)
     _check_out(res["out"][rows], want, f"random short chunk {H}/{Hkv} d{d} prefix {prefix} c {c}")
+
+
+@pytest.mark.parametrize("d,step_log2", [(128, 0.05), (128, 0.4), (64, 2.0)])
+def test_rising_scores_move_the_reference(d, step_log2):
+    """Scores that climb steadily with the key position (by step_log2 per key in log2 units, i.e. by 3 to
+    128 per 64-key tile): the exponent reference has to be moved again and again, and for the steepest
+    case every row is decided by its last few keys.  Rotary embedding off so that the ramp survives."""
+    import math
+    C, H, Hkv = 1500, 4, 2
+    rng = np.random.default_rng(9)
+    scale = synth.default_scale(d)
+    u = rng.standard_normal(d).astype(np.float32)
+    u /= np.linalg.norm(u)
+    qn = 4.0
+    # k_j = u * j * step / (scale * log2(e) * qn)  ->  scale * <q, k_j> * log2(e) = step * j for q = qn * u
+    ramp = (np.arange(C, dtype=np.float32) * (step_log2 / (scale * math.log2(math.e) * qn)))[:, None, None]
+    k = synth.f32_to_bf16_bits(ramp * u[None, None, :] + 0.05 * rng.standard_normal((C, Hkv, d)).astype(np.float32))
+    q = synth.f32_to_bf16_bits(qn * u[None, None, :] + 0.05 * rng.standard_normal((C, H, d)).astype(np.float32))
+    v = synth.normal_bf16(9, 35, 2, (C, Hkv, d))
+    from gpu_pipeline import run_chunked
+    res = run_chunked(q, k, v, [0, 700, 701, C], scale, None)
+    want = orc.causal_attention(_f64(q), _f64(k), _f64(v), scale, rope_base=None)
+    mx, mean = _check_out(res["out"], want, f"rising scores d{d} step {step_log2}")
+    print(f"rising scores d{d} step {step_log2}: max-abs {mx:.3e} mean-abs {mean:.3e}")
