@@ -46,7 +46,9 @@ typedef __attribute__((address_space(1))) const void gbl_void;
 
 constexpr int kWaves = 8;              // waves per workgroup
 constexpr int kThreads = 64 * kWaves;
-constexpr int kBN = 64;                // keys per tile
+// keys per tile: 64 at head_dim 128; 128 at head_dim 64, where a 64-key tile holds too little MFMA
+// work (16 per wave) to carry the two barriers of a tile step
+constexpr int key_tile(int D) { return D == 64 ? 128 : 64; }
 constexpr int kStages = 3;             // LDS ring depth for K and for V tiles
 constexpr float kSumLimit = 1048576.0f; // partial row sum (32 weights) beyond which the reference is moved
 constexpr float kNoKeyYet = -1e30f;    // exponent reference of a row before its first visible key
@@ -64,6 +66,7 @@ struct AttnArgs {
   int nq_tiles;      // row tiles per kv head
   int rows_per_wg;   // virtual rows per workgroup: 32 * (active waves), <= 256
   float c_log2;      // scale * log2(e): softmax runs in base 2
+  int bn;            // keys per tile, key_tile(head_dim)
   // key-split launches only
   float* scratch;    // partial results, one slot per (split unit, key segment)
   int n_whole;       // workgroups [0, n_whole) take whole units
@@ -87,7 +90,7 @@ __device__ __forceinline__ void unit_of(const AttnArgs& a, int u, int* g, int* q
 }
 __device__ __forceinline__ int unit_steps(const AttnArgs& a, int qt) {
   const int row_hi = min((qt + 1) * a.rows_per_wg, a.chunk * a.G);   // exclusive, in virtual rows
-  return (a.prefix + (row_hi - 1) / a.G) / kBN + 1;                  // key tiles the row tile walks
+  return (a.prefix + (row_hi - 1) / a.G) / a.bn + 1;                 // key tiles the row tile walks
 }
 constexpr int kPartialFloats(int D) { return kWaves * (D / 32 * 16 + 2) * 64; }   // per scratch slot
 
@@ -115,7 +118,8 @@ __device__ __forceinline__ void lds_dma16(const void* uniform_base, unsigned lan
 template <int D>
 __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, const int g, const int qt,
                                        const int jt0, const int jt1, float* partial) {
-  constexpr int BN = kBN;
+  constexpr int BN = key_tile(D);
+  constexpr int MB = BN / 32;              // 32-key blocks of a tile
   constexpr int CPR = D / 8;               // 16-byte pieces per K/V row
   constexpr int KS = D / 16;               // contraction steps of S^T = K Q^T
   constexpr int DB = D / 32;               // 32-row blocks of O^T
@@ -238,10 +242,10 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, const int
   __syncthreads();
   if (phase == 1) __syncthreads();   // second group runs one barrier behind the first
 
-  f32x16 s[2];
-  bf16x8 pf[2][2];
+  f32x16 s[MB];
+  bf16x8 pf[MB][2];
 #pragma unroll
-  for (int mb = 0; mb < 2; ++mb)
+  for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
     for (int si = 0; si < 2; ++si)
 #pragma unroll
@@ -276,16 +280,16 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, const int
         return __builtin_bit_cast(bf16x8, vf);
       };
       auto kread = [&](int idx) -> bf16x8 {
-        const int ks = idx / 2, mb = idx % 2;
+        const int ks = idx / MB, mb = idx % MB;
         return Kb[(32 * mb + n) * CPR + ((2 * ks + kg) ^ k_sw)];
       };
-      constexpr int N0 = 4 * DB, N = N0 + 2 * KS;
+      constexpr int N0 = 2 * MB * DB, N = N0 + MB * KS;
       auto frag = [&](int i) -> bf16x8 { return (i < N0) ? vread(i) : kread(i - N0); };
       bf16x8 fq[PF];
 #pragma unroll
       for (int i = 0; i < PF; ++i) fq[i] = frag(i);
 #pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
+      for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
         for (int e = 0; e < 16; ++e) s[mb][e] = 0.0f;
       __builtin_amdgcn_sched_barrier(0);
@@ -298,7 +302,7 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, const int
           o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, pf[mb][si], o[db], 0, 0, 0);
         } else {
           const int q = i - N0;
-          s[q % 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, qf[q / 2], s[q % 2], 0, 0, 0);
+          s[q % MB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, qf[q / MB], s[q % MB], 0, 0, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -318,7 +322,7 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, const int
         // counters that are kept up to date (and kept in registers) on every tile
         asm volatile("" : "+v"(rel));
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
+        for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
           for (int e = 0; e < 16; ++e)
             if (32 * mb + 8 * (e / 4) + (e % 4) > rel) s[mb][e] = -INFINITY;
@@ -332,7 +336,7 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, const int
         const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
         float sum0 = 0.0f, sum1 = 0.0f;
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
+        for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
           for (int e = 0; e < 16; e += 2) {
             const float p0 = __builtin_amdgcn_exp2f(fmaf(s[mb][e], c, -m));
@@ -353,7 +357,7 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, const int
       if (__builtin_amdgcn_ballot_w64(!(psum < kSumLimit)) != 0) {
         float tmax = s[0][0];
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
+        for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
           for (int e = 0; e < 16; ++e) tmax = fmaxf(tmax, s[mb][e]);
         tmax = fmaxf(tmax, other_half(tmax)) * c;
@@ -539,7 +543,8 @@ int launch_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
   a.segments = 1;
   const int64_t units = tiles * n_kv_heads;
   if (units > 0x7FFFFFFF) return KVRA_EUNSUPPORTED;
-  const unsigned smem = 2u * kStages * kBN * static_cast<unsigned>(head_dim) * 2u;   // K ring + V ring
+  a.bn = key_tile(head_dim);
+  const unsigned smem = 2u * kStages * static_cast<unsigned>(a.bn) * static_cast<unsigned>(head_dim) * 2u;   // K ring + V ring
   const dim3 b3(kThreads);
 
   // Key-split launch, for launches with fewer units than CUs: every unit is cut into S key
@@ -555,7 +560,7 @@ int launch_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
     const int64_t rest = units % cus;
     // shortest split unit = the last row tile
     const int64_t last_rows = std::min<int64_t>(a.rows_per_wg, vrows);
-    const int64_t min_steps = (prefix_len + (last_rows - 1) / G) / kBN + 1;
+    const int64_t min_steps = (prefix_len + (last_rows - 1) / G) / a.bn + 1;
     int best = 1;
     if (rest > 0 && units < cus) {
       double t[kMaxSegments + 1], t_min = 1.0;
