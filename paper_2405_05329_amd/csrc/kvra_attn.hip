@@ -42,7 +42,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 typedef __attribute__((address_space(3))) void lds_void;
-typedef __attribute__((address_space(1))) const void gbl_void;
 
 constexpr int kWaves = 8;              // waves per workgroup
 constexpr int kThreads = 64 * kWaves;
@@ -50,7 +49,7 @@ constexpr int kThreads = 64 * kWaves;
 // work (16 per wave) to carry the two barriers of a tile step
 constexpr int key_tile(int D) { return D == 64 ? 128 : 64; }
 constexpr int kStages = 3;             // LDS ring depth for K and for V tiles
-constexpr float kSumLimit = 1048576.0f; // partial row sum (32 weights) beyond which the reference is moved
+constexpr float kSumLimit = 1048576.0f; // a lane's partial row sum over one tile beyond which the reference is moved
 constexpr float kNoKeyYet = -1e30f;    // exponent reference of a row before its first visible key
 
 struct AttnArgs {
@@ -215,9 +214,9 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, const int
 #pragma unroll
     for (int e = 0; e < 16; ++e) o[db][e] = 0.0f;
   // exponent reference of the row (scaled by c_log2); trails the running max by a bounded amount
-  // (see kSumLimit).  A huge negative
-  // FINITE start value: a row that has not met a visible key yet (possible when a fragment starts
-  // beyond the row's last key) then yields p = exp2(-inf) = 0 and alpha = exp2(0) = 1, never NaN.
+  // (see kSumLimit).  A huge negative FINITE start value: a row that has not met a visible key
+  // yet (possible when a fragment starts beyond the row's last key) then yields p = exp2(-inf) = 0
+  // and alpha = exp2(0) = 1, never NaN.
   float m = kNoKeyYet;
   float l = 0.0f;        // running row sum of this lane's half of the keys
   const float c = a.c_log2;
