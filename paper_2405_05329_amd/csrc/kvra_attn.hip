@@ -20,12 +20,13 @@
 // barrier after each block.  The second group starts one barrier late, so while one group keeps
 // the matrix pipe busy its SIMD partner does exp2/max/sum on the vector ALU ("ping-pong").
 //
-// Launch shapes.  Normally one workgroup per unit (kv head, 256-row tile), every unit whole.  A
-// launch with fewer units than CUs (a short chunk behind a long prefix) cuts every unit into S
-// equal key segments instead, one workgroup per segment, issued segment by segment so that the row
-// tiles of a head still sweep the same keys at the same time (which is what lets them share the
-// K/V stream in L2).  The un-normalised pieces go through a per-device scratch buffer to a small
-// fix-up kernel that merges them (the usual log-sum-exp merge).
+// Launch shapes.  Normally one workgroup per unit (kv head, 256-row tile), every unit whole.  When
+// the units do not fill the last round of CUs (160 or 320 units on 256 CUs; a handful of very long
+// units for a short chunk behind a long prefix), the units of that round are cut into S equal key
+// segments each, one workgroup per segment, issued segment by segment so that the row tiles of a
+// head still sweep the same keys at the same time (which is what lets them share the K/V stream in
+// L2).  The un-normalised pieces go through a per-device scratch buffer to a small fix-up kernel
+// that merges them (the usual log-sum-exp merge).
 #include "kvra_internal.h"
 
 #include <algorithm>
@@ -546,12 +547,11 @@ int launch_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
   const unsigned smem = 2u * kStages * static_cast<unsigned>(a.bn) * static_cast<unsigned>(head_dim) * 2u;   // K ring + V ring
   const dim3 b3(kThreads);
 
-  // Key-split launch, for launches with fewer units than CUs: every unit is cut into S key
-  // segments.  Time in units of a whole row tile: 1 without the split, t(S) = ceil(units * S / CUs) / S
-  // with it.  Feasible S: one scratch slot per piece (2 per CU) and at least kMinSteps key tiles per
-  // piece.  Taken: the smallest S within a tenth of the best t, if that is at most 0.5.  (Filling the
-  // chip from 60-75 % to 100 % does not pay on this power-managed part: the busy CUs clock higher
-  // when the others idle - measured +0..5 % after the cost of the extra traffic and the fix-up.)
+  // Key-split launch: the units beyond the last full round of CUs (all of them when there are fewer
+  // units than CUs) are cut into S key segments each.  Time of that last round in units of a whole
+  // row tile: 1 without the split, t(S) = ceil(rest * S / CUs) / S with it.  Feasible S: one scratch
+  // slot per piece (2 per CU) and at least kMinSteps key tiles per piece.  Taken: the smallest S within
+  // a tenth of the best t, if that is at most 0.8.
   constexpr int kMinSteps = 16, kMaxSegments = 16;
   int cus = 0;
   float* scratch = device_scratch(&cus);
@@ -561,7 +561,7 @@ int launch_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
     const int64_t last_rows = std::min<int64_t>(a.rows_per_wg, vrows);
     const int64_t min_steps = (prefix_len + (last_rows - 1) / G) / a.bn + 1;
     int best = 1;
-    if (rest > 0 && units < cus) {
+    if (rest > 0) {
       double t[kMaxSegments + 1], t_min = 1.0;
       int s_max = 1;
       for (int S = 2; S <= kMaxSegments; ++S) {
@@ -571,7 +571,7 @@ int launch_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
         s_max = S;
       }
       for (int S = 2; S <= s_max; ++S)
-        if (t[S] <= 0.5 && t[S] <= 1.1 * t_min) { best = S; break; }
+        if (t[S] <= 0.8 && t[S] <= 1.1 * t_min) { best = S; break; }
     }
     if (best > 1) {
       a.scratch = scratch;
