@@ -15,7 +15,7 @@
  *   - Return value: KVRA_OK, or a negative code; on error nothing was enqueued.
  *   - head_dim must be 64 or 128; n_q_heads must be a multiple of n_kv_heads; query head h
  *     reads key/value head h / (n_q_heads / n_kv_heads).
- *   - The only state the library keeps is one scratch buffer per device (about 70 MB, hipMalloc'ed
+ *   - The only state the library keeps is one scratch buffer per device (about 100 MB, hipMalloc'ed
  *     by the first kvra_chunk_attn call on that device, kept until the process ends).  It holds
  *     the partial results of key-split launches, which kvra_chunk_attn takes when a call has fewer
  *     (kv head, 256-row tile) units than the device has CUs - a short chunk behind a long prefix.

@@ -486,8 +486,10 @@ __global__ __launch_bounds__(64) void chunk_attn_fixup_kernel(AttnArgs a) {
 
 namespace {
 
-// Per-device scratch of the key-split path: two partial-result slots per CU, allocated on first
-// use and kept until the process ends.
+// Per-device scratch of the key-split path: kSlotsPerCu partial-result slots per CU (192 units on
+// 256 CUs need four pieces per unit to gain anything), allocated on first use and kept until the
+// process ends.
+constexpr int kSlotsPerCu = 3;
 constexpr int kMaxDevices = 16;
 float* g_scratch[kMaxDevices] = {};
 int g_cus[kMaxDevices] = {};
@@ -502,7 +504,7 @@ float* device_scratch(int* cus_out) {
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 8) cus = -1;
     g_cus[dev] = cus;
     if (cus > 0) {
-      const size_t bytes = static_cast<size_t>(2) * cus * kPartialFloats(128) * sizeof(float);
+      const size_t bytes = static_cast<size_t>(kSlotsPerCu) * cus * kPartialFloats(128) * sizeof(float);
       void* p = nullptr;
       if (hipMalloc(&p, bytes) == hipSuccess) g_scratch[dev] = static_cast<float*>(p);
       else (void)hipGetLastError();   // leave no sticky error behind; the plain launch needs no scratch
@@ -550,7 +552,7 @@ int launch_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
   // Key-split launch: the units beyond the last full round of CUs (all of them when there are fewer
   // units than CUs) are cut into S key segments each.  Time of that last round in units of a whole
   // row tile: 1 without the split, t(S) = ceil(rest * S / CUs) / S with it.  Feasible S: one scratch
-  // slot per piece (2 per CU) and at least kMinSteps key tiles per piece.  Taken: the smallest S within
+  // slot per piece (kSlotsPerCu per CU) and at least kMinSteps key tiles per piece.  Taken: the smallest S within
   // a tenth of the best t, if that is at most 0.8.
   constexpr int kMinSteps = 16, kMaxSegments = 16;
   int cus = 0;
@@ -565,7 +567,7 @@ int launch_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
       double t[kMaxSegments + 1], t_min = 1.0;
       int s_max = 1;
       for (int S = 2; S <= kMaxSegments; ++S) {
-        if (rest * S > 2 * static_cast<int64_t>(cus) || min_steps / S < kMinSteps) break;
+        if (rest * S > kSlotsPerCu * static_cast<int64_t>(cus) || min_steps / S < kMinSteps) break;
         t[S] = static_cast<double>((rest * S + cus - 1) / cus) / S;
         t_min = std::min(t_min, t[S]);
         s_max = S;
