@@ -17,8 +17,9 @@
  *     reads key/value head h / (n_q_heads / n_kv_heads).
  *   - The only state the library keeps is one scratch buffer per device (about 100 MB, hipMalloc'ed
  *     by the first kvra_chunk_attn call on that device, kept until the process ends).  It holds
- *     the partial results of key-split launches, which kvra_chunk_attn takes when a call has fewer
- *     (kv head, 256-row tile) units than the device has CUs - a short chunk behind a long prefix.
+ *     the partial results of key-split launches, which kvra_chunk_attn takes when the (kv head,
+ *     256-row tile) units of a call do not fill the last round of the device's CUs - e.g. a short
+ *     chunk behind a long prefix.
  *     Two such calls (kvra_layer_chunk included) that overlap in time on one device, from
  *     different streams, would share it and are not supported.  If the allocation fails the call
  *     runs without key-splitting.
