@@ -16,9 +16,20 @@
 //
 // Schedule.  A workgroup is 8 waves = two groups of 4 (one wave of each group per SIMD).  Per key
 // tile a wave runs an MFMA block (P.V of the previous tile, then K.Q^T of this one: 32 MFMAs at
-// d = 128) and a VALU block (softmax of this tile, staging of future K/V tiles), with a workgroup
-// barrier after each block.  The second group starts one barrier late, so while one group keeps
-// the matrix pipe busy its SIMD partner does exp2/max/sum on the vector ALU ("ping-pong").
+// d = 128) and a VALU block (softmax of this tile, staging of future K/V tiles).  While one group
+// keeps the matrix pipe busy its SIMD partner does the exponentials on the vector ALU
+// ("ping-pong").  At d = 64 there is a workgroup barrier after each block and the second group
+// starts one barrier late.  At d = 128 there is one barrier per tile step: the first group runs
+// [MFMA block, VALU block, barrier], the second [VALU block of the previous tile, MFMA block,
+// barrier]; the barrier puts the groups back into opposite phases, and in between a group that is
+// done with its vector work starts on the matrix pipe at once instead of waiting for its partner.
+//
+// Softmax arithmetic.  scale * log2(e) is folded into the Q fragment (one more bf16 rounding of
+// Q, of the size the rotation already made) and the score accumulators start at minus the row's
+// exponent reference m, so the MFMAs hand back  s = scale log2(e) q.k - m  and a weight is one
+// exp2 away.  No row maximum is formed on the way (see kSumLimit).  Every instruction of the VALU
+// block costs issue time the matrix pipe of the partner wave waits for, scalar ones included, and
+// v_dot2c_f32_bf16 queues behind the partner's MFMAs: the block is kept to exp2, add and convert.
 //
 // Launch shapes.  Normally one workgroup per unit (kv head, 256-row tile), every unit whole.  When
 // the units do not fill the last round of CUs (160 or 320 units on 256 CUs; a handful of very long
@@ -50,6 +61,8 @@ constexpr int kThreads = 64 * kWaves;
 // work (16 per wave) to carry the two barriers of a tile step
 constexpr int key_tile(int D) { return D == 64 ? 128 : 64; }
 constexpr int kStages = 3;             // LDS ring depth for K and for V tiles
+// barriers per tile step: one at head_dim 128 (measured +4..5 %), two at head_dim 64 (one: -4 %)
+constexpr bool one_barrier(int D) { return D == 128; }
 constexpr float kSumLimit = 1048576.0f; // a lane's partial row sum over one tile beyond which the reference is moved
 constexpr float kNoKeyYet = -1e30f;    // exponent reference of a row before its first visible key
 
@@ -112,6 +125,17 @@ __device__ __forceinline__ void lds_dma16(const void* uniform_base, unsigned lan
                : "memory", "m0");
 }
 
+// The same under a wave-uniform switch: with on_mask = 0 the instruction is issued with no lanes
+// enabled and moves nothing (no branch around it, so that it can sit in straight-line code).
+__device__ __forceinline__ void lds_dma16_if(unsigned long long on_mask, const void* uniform_base,
+                                             unsigned lane_byte_off, unsigned lds_byte_addr) {
+  unsigned long long saved;
+  asm volatile("s_mov_b32 m0, %3\n\ts_and_saveexec_b64 %0, %4\n\tglobal_load_lds_dwordx4 %1, %2\n\ts_mov_b64 exec, %0"
+               : "=&s"(saved)
+               : "v"(lane_byte_off), "s"(uniform_base), "s"(lds_byte_addr), "s"(on_mask)
+               : "memory", "m0", "scc");
+}
+
 // One fragment of work: the queries of row tile qt of kv head g against key tiles [jt0, jt1).
 // partial == nullptr: the fragment covers all the keys the tile needs, O / l goes to a.out.
 // Otherwise the un-normalised state (O, m, l per lane) goes to partial for the fix-up kernel.
@@ -127,6 +151,8 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, const int
   constexpr int TILE = BN * CPR;           // 16-byte pieces per tile
   constexpr int LOADS = TILE / kThreads;   // pieces each thread moves per tile
   constexpr int PF = 4;                    // LDS operand reads kept in flight ahead of the MFMAs
+  // One workgroup barrier per tile step instead of two (see "Schedule" at the top of the file).
+  constexpr bool ONE_BARRIER = one_barrier(D);
   static_assert(TILE % kThreads == 0, "tile must split evenly over the workgroup");
 
   // smem: K ring then V ring, kStages tiles each
@@ -156,12 +182,17 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, const int
   // key tiles of the fragment this wave needs (its rows see keys up to wmax)
   const int jw = wave_active ? min(max(wmax / BN + 1 - jt0, 0), nt) : 0;
 
-  // Q fragment: B operand of S^T, lane (n, kg) holds Q[row n][16 ks + 8 kg .. +7]
+  // Q fragment: B operand of S^T, lane (n, kg) holds Q[row n][16 ks + 8 kg .. +7], times
+  // scale * log2(e) (rounded to bf16 again)
   bf16x8 qf[KS];
   {
     const __bf16* qrow = a.q + (static_cast<long long>(r) * a.H + h) * D;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qrow + 16 * ks + 8 * kg);
+    for (int ks = 0; ks < KS; ++ks) {
+      const bf16x8 raw = *reinterpret_cast<const bf16x8*>(qrow + 16 * ks + 8 * kg);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) qf[ks][e] = static_cast<__bf16>(static_cast<float>(raw[e]) * a.c_log2);
+    }
   }
 
   // ---- global -> LDS staging of K/V tiles (LDS-direct loads, no registers in between) ---------
@@ -184,6 +215,16 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, const int
     koff[i] = 2u * (static_cast<unsigned>(ld_row[i]) * row_stride + ld_kcc[i]);   // bytes
     voff[i] = 2u * (static_cast<unsigned>(ld_row[i]) * row_stride + ld_vcc[i]);
   }
+  // offsets for the one tile that straddles the end of the cache: rows past the end repeat the last valid row
+  unsigned koff_last[LOADS], voff_last[LOADS];
+  {
+    const int lim_last = (total - 1) % BN;
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+      koff_last[i] = 2u * (static_cast<unsigned>(min(ld_row[i], lim_last)) * row_stride + ld_kcc[i]);
+      voff_last[i] = 2u * (static_cast<unsigned>(min(ld_row[i], lim_last)) * row_stride + ld_vcc[i]);
+    }
+  }
   const __bf16* kbase = a.k + static_cast<long long>(g) * D;
   const __bf16* vbase = a.v + static_cast<long long>(g) * D;
 
@@ -192,13 +233,21 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, const int
                       int kt, u32x4* dst) {
     const __bf16* base = head_base + static_cast<long long>(jt0 + kt) * BN * row_stride;
     const int lim = total - 1 - (jt0 + kt) * BN;
+    if (lim >= BN - 1) {   // whole tile inside the cache: the precomputed offsets (a real branch, wave-uniform)
 #pragma unroll
-    for (int i = 0; i < LOADS; ++i) {
-      const unsigned o32 = (lim >= BN - 1) ? off[i]
-                                           : 2u * (static_cast<unsigned>(min(ld_row[i], lim)) * row_stride + cc[i]);
-      const unsigned lds_addr = static_cast<unsigned>(reinterpret_cast<uintptr_t>(
-          (lds_void*)(dst + (i * kWaves + wave) * 64)));
-      lds_dma16(base, o32, lds_addr);
+      for (int i = 0; i < LOADS; ++i) {
+        const unsigned lds_addr = static_cast<unsigned>(reinterpret_cast<uintptr_t>(
+            (lds_void*)(dst + (i * kWaves + wave) * 64)));
+        lds_dma16(base, off[i], lds_addr);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < LOADS; ++i) {
+        const unsigned o32 = 2u * (static_cast<unsigned>(min(ld_row[i], lim)) * row_stride + cc[i]);
+        const unsigned lds_addr = static_cast<unsigned>(reinterpret_cast<uintptr_t>(
+            (lds_void*)(dst + (i * kWaves + wave) * 64)));
+        lds_dma16(base, o32, lds_addr);
+      }
     }
   };
   // staging step s moves K tile s+1 and V tile s; returns the number of loads it issued
@@ -214,13 +263,17 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, const int
   for (int db = 0; db < DB; ++db)
 #pragma unroll
     for (int e = 0; e < 16; ++e) o[db][e] = 0.0f;
-  // exponent reference of the row (scaled by c_log2); trails the running max by a bounded amount
-  // (see kSumLimit).  A huge negative FINITE start value: a row that has not met a visible key
-  // yet (possible when a fragment starts beyond the row's last key) then yields p = exp2(-inf) = 0
-  // and alpha = exp2(0) = 1, never NaN.
+  // exponent reference of the row (in base-2 score units); trails the running max by a bounded
+  // amount (see kSumLimit).  kNoKeyYet marks a row that has not met a visible key yet (possible
+  // when a fragment starts beyond the row's last key): its scores are formed against 0 and its
+  // first visible keys send the wave through the exact path, which sets the reference.
   float m = kNoKeyYet;
   float l = 0.0f;        // running row sum of this lane's half of the keys
-  const float c = a.c_log2;
+  // start value of the score accumulators: minus the exponent reference (0 while the row has none),
+  // so that the MFMAs deliver  s c - m  directly (c is folded into the Q fragment)
+  f32x16 sref;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) sref[e] = 0.0f;
 
   // lane-constant parts of the LDS read addresses
   const int k_sw = (n / RPB) % CPR;                       // K swizzle of row 32 mb + n
@@ -229,6 +282,21 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, const int
   const int v_sw = 4 * ((v_row0 / RPB) % (D / 32));
   const int v_cc0 = 2 * vmh + ((vi & 3) >> 1);            // + 4 db
   const int v_sub = (vi & 1) * 4;                         // element offset inside the 16-byte piece
+
+  // Staging state of the tile loop.  At tile step j this wave (st = j + phase) sends off its pieces of
+  // K tile st + 2 and V tile st + 1: two running pointers, advanced by one tile per step, and the
+  // LDS byte addresses of the ring slots in the order this wave meets them (slot_k[r] is where the K
+  // tile goes at a step with j % kStages == r; the V tile of that step goes to slot_v[r]).
+  const long long tile_elems = static_cast<long long>(BN) * row_stride;
+  const __bf16* kp = kbase + (jt0 + 2 + phase) * tile_elems;
+  const __bf16* vp = vbase + (jt0 + 1 + phase) * tile_elems;
+  const int kt_ragged = (total % BN != 0) ? (total - 1) / BN - jt0 : -1;   // the tile that straddles the end
+  unsigned slot_k[kStages], slot_v[kStages];
+#pragma unroll
+  for (int r = 0; r < kStages; ++r) {
+    slot_k[r] = static_cast<unsigned>(reinterpret_cast<uintptr_t>((lds_void*)(ldsK((r + 2 + phase) % kStages) + wave * 64)));
+    slot_v[r] = static_cast<unsigned>(reinterpret_cast<uintptr_t>((lds_void*)(ldsV((r + 1 + phase) % kStages) + wave * 64)));
+  }
 
   // ---- prologue: K tiles 0..2 and V tiles 0..1 on their way into LDS -----------------------------
   // the first MFMA block multiplies a zero P by the ring slot "before" V tile 0: make it finite
@@ -240,7 +308,7 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, const int
   // loop entry would make the compiler guard the loop's MFMAs with vmcnt waits
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
   __syncthreads();
-  if (phase == 1) __syncthreads();   // second group runs one barrier behind the first
+  if (!ONE_BARRIER && phase == 1) __syncthreads();   // second group runs one barrier behind the first
 
   f32x16 s[MB];
   bf16x8 pf[MB][2];
@@ -288,10 +356,6 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, const int
       bf16x8 fq[PF];
 #pragma unroll
       for (int i = 0; i < PF; ++i) fq[i] = frag(i);
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) s[mb][e] = 0.0f;
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < N; ++i) {
@@ -300,20 +364,40 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, const int
         if (i < N0) {
           const int mb = i / (2 * DB), si = (i / DB) % 2, db = i % DB;
           o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, pf[mb][si], o[db], 0, 0, 0);
-        } else {
+        } else
+        {
           const int q = i - N0;
-          s[q % MB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, qf[q / MB], s[q % MB], 0, 0, 0);
+          s[q % MB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, qf[q / MB], q < MB ? sref : s[q % MB], 0, 0, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
     }
-    __syncthreads();
+    if (!ONE_BARRIER || phase == 1) __syncthreads();
 
     // ================= VALU block =================
     // staging: this wave's step is j + phase (the late group is one tile ahead in tile numbers);
     // tiles K(st+2), V(st+1) start their trip now and are awaited one period later
     const int st = j + phase;
-    const int issued = (st >= 1) ? stage(st + 1) : 0;
+    // The 2 LOADS loads are handed out one at a time and spread over the softmax below.  A tile
+    // beyond the fragment is "loaded" with no lane enabled: no branch, so the loads can sit in
+    // straight-line code.  The ragged last tile of the cache takes the clamped offsets.
+    const bool k_on = st >= 1 && st + 2 < nt, v_on = st >= 1 && st + 1 < nt;
+    const int issued = (k_on ? LOADS : 0) + (v_on ? LOADS : 0);
+    const unsigned long long k_mask = __builtin_amdgcn_ballot_w64(k_on), v_mask = __builtin_amdgcn_ballot_w64(v_on);
+    const bool k_rag = st + 2 == kt_ragged, v_rag = st + 1 == kt_ragged;
+    auto stage_piece = [&](int idx) __attribute__((always_inline)) {
+      __builtin_amdgcn_sched_barrier(0);
+      if (idx < LOADS)
+        lds_dma16_if(k_mask, kp, k_rag ? koff_last[idx] : koff[idx], slot_k[RS] + idx * (kWaves * 64 * 16));
+      else
+        lds_dma16_if(v_mask, vp, v_rag ? voff_last[idx - LOADS] : voff[idx - LOADS],
+                     slot_v[RS] + (idx - LOADS) * (kWaves * 64 * 16));
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    if (j >= jw) {
+#pragma unroll
+      for (int idx = 0; idx < 2 * LOADS; ++idx) stage_piece(idx);
+    }
     if (j < jw) {
       // register e of block mb is key  j*BN + 32 mb + 8 (e/4) + 4 kg + e%4  of query n
       if ((jt0 + j) * BN + BN - 1 > wmin) {
@@ -321,63 +405,86 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, const int
         // opaque to the optimiser: otherwise the 32 compares below become 32 loop-carried
         // counters that are kept up to date (and kept in registers) on every tile
         asm volatile("" : "+v"(rel));
+        const float ninf = -INFINITY;
+        // compare and select one element at a time through vcc (written out: left to itself the
+        // compiler keeps all 32 lane masks alive in scalar registers, which spills others)
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-          for (int e = 0; e < 16; ++e)
-            if (32 * mb + 8 * (e / 4) + (e % 4) > rel) s[mb][e] = -INFINITY;
+          for (int e = 0; e < 16; ++e) {
+            float x = s[mb][e];
+            asm volatile("v_cmp_gt_i32 vcc, %1, %2\n\tv_cndmask_b32 %0, %0, %3, vcc"
+                         : "+v"(x)
+                         : "n"(32 * mb + 8 * (e / 4) + (e % 4)), "v"(rel), "v"(ninf)
+                         : "vcc");
+            s[mb][e] = x;
+          }
       }
       // ---- online softmax (base 2) with a lazily moved exponent reference -------------------
-      // weights of this tile against the current reference: p = exp2(s c - m), rounded to bf16 in
-      // pairs; the row sum adds up the rounded values (v_dot2 with ones), i.e. exactly the weights
-      // the P.V product uses.  Returns this lane's part of the row sum.
-      auto weights = [&]() __attribute__((always_inline)) -> float {
+      // weights of this tile: p = exp2(s) against the reference in force (MOVED: exp2(s - delta)
+      // against one that was just raised by delta), rounded to bf16 in pairs for the P.V product;
+      // the row sum adds the unrounded values.  Returns this lane's part of the row sum.  The first
+      // pass also carries the staging loads, one every few exponentials.
+      auto weights = [&](auto moved_tag, const float delta) __attribute__((always_inline)) -> float {
+        constexpr bool MOVED = decltype(moved_tag)::value;
         typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-        const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
         float sum0 = 0.0f, sum1 = 0.0f;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
           for (int e = 0; e < 16; e += 2) {
-            const float p0 = __builtin_amdgcn_exp2f(fmaf(s[mb][e], c, -m));
-            const float p1 = __builtin_amdgcn_exp2f(fmaf(s[mb][e + 1], c, -m));
+            if constexpr (!MOVED) {
+              constexpr int PAIRS = MB * 8, EVERY = PAIRS / (2 * LOADS);
+              const int pair = mb * 8 + e / 2;
+              if (pair % EVERY == 0) stage_piece(pair / EVERY);
+            }
+            const float p0 = __builtin_amdgcn_exp2f(MOVED ? s[mb][e] - delta : s[mb][e]);
+            const float p1 = __builtin_amdgcn_exp2f(MOVED ? s[mb][e + 1] - delta : s[mb][e + 1]);
             const bf16x2 pp = {static_cast<__bf16>(p0), static_cast<__bf16>(p1)};
-            if ((e / 2) % 2) sum1 = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, sum1, false);
-            else sum0 = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, sum0, false);
+            if ((e / 2) % 2) sum1 += p0 + p1;
+            else sum0 += p0 + p1;
             pf[mb][e / 8][e % 8] = pp[0];
             pf[mb][e / 8][e % 8 + 1] = pp[1];
           }
         return sum0 + sum1;
       };
       // Optimistic pass: no row maximum is formed.  As long as the scores stay within reach of m the
-      // weights are modest; a lane whose partial sum gets out of hand (or is inf: a row's first
-      // visible keys, m = kNoKeyYet) sends the whole wave through the exact path: row maximum,
-      // m, l and O re-based to it, weights formed again.
-      float psum = weights();
-      if (__builtin_amdgcn_ballot_w64(!(psum < kSumLimit)) != 0) {
-        float tmax = s[0][0];
+      // weights are modest; a lane whose partial sum gets out of hand, or whose row has no reference
+      // yet, sends the whole wave through the exact path: row maximum, m, l, O and the accumulator
+      // start value re-based to it, weights formed again.
+      float psum = weights(std::false_type{}, 0.0f);
+      const bool unset = m == kNoKeyYet;
+      if (__builtin_amdgcn_ballot_w64(!(psum < kSumLimit) || unset) != 0) {
+        float tmax = s[0][0];   // relative to the reference in force
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
           for (int e = 0; e < 16; ++e) tmax = fmaxf(tmax, s[mb][e]);
-        tmax = fmaxf(tmax, other_half(tmax)) * c;
-        const float mnew = fmaxf(m, tmax);
-        const float alpha = __builtin_amdgcn_exp2f(m - mnew);
+        tmax = fmaxf(tmax, other_half(tmax));
+        // a row without reference takes its maximum as one, once it has met a visible key
+        const bool seen = tmax > -INFINITY;
+        const float delta = unset ? (seen ? tmax : 0.0f) : fmaxf(tmax, 0.0f);
+        const float alpha = unset ? 1.0f : __builtin_amdgcn_exp2f(-delta);
+        if (unset) { if (seen) m = tmax; }
+        else m += delta;
         l *= alpha;
-        m = mnew;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
           for (int e = 0; e < 16; ++e) o[db][e] *= alpha;
-        psum = weights();
+#pragma unroll
+        for (int e = 0; e < 16; ++e) sref[e] -= delta;
+        psum = weights(std::true_type{}, delta);
       }
       l += psum;
     }
+    kp += tile_elems;
+    vp += tile_elems;
     // everything issued before this block (tiles K(st+1), V(st)) must have landed before the barrier
     if (issued == 2 * LOADS) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * LOADS));
     else if (issued == LOADS) __builtin_amdgcn_s_waitcnt(0x0F70 | LOADS);
     else __builtin_amdgcn_s_waitcnt(0x0F70);
-    __syncthreads();
+    if (!ONE_BARRIER || phase == 0) __syncthreads();
   };
   for (int j0 = 0; j0 <= nt; j0 += kStages) {
     tile_step(j0, std::integral_constant<int, 0>{});
@@ -385,7 +492,7 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, const int
     if (j0 + 2 <= nt) tile_step(j0 + 2, std::integral_constant<int, 2>{});
   }
   static_assert(kStages == 3, "the unrolled loop above is written for a ring of three");
-  if (phase == 0) __syncthreads();   // both groups execute the same number of barriers
+  if (!ONE_BARRIER && phase == 0) __syncthreads();   // both groups execute the same number of barriers
 
   // ---- epilogue: O / l, bf16, store -----------------------------------------------------------
   if (partial != nullptr) {

@@ -137,16 +137,20 @@ def test_no_rope_and_other_scale():
 
 def test_peaky_softmax_exercises_the_rescale_path():
     # Queries four times larger: scores have std 4, row maxima keep moving as tiles stream in and
-    # the softmax is dominated by a few keys.  The bf16 rounding of the rotated Q and K (an input
-    # effect, 2^-9 relative per operand) is amplified four-fold in the exponent here, so the kernel
-    # is held to the standard bars against the oracle evaluated on the oracle's own correctly
-    # rounded rotation, and to four times wider bars against the un-rounded oracle.
+    # the softmax is dominated by a few keys.  The bf16 roundings of the operands of the score
+    # product (2^-9 relative each: the rotated Q and K, and the kernel's Q fragment, which carries
+    # scale * log2(e) and is rounded once more) are amplified four-fold in the exponent here, so
+    # the kernel is held to the standard bars against the oracle evaluated on operands the oracle
+    # rounded the same way itself, and to four times wider bars against the un-rounded oracle.
     C, H, Hkv, d = 700, 4, 4, 128
     q, k, v, scale, res = _run(52, 2, C, H, Hkv, d, [0, 300, 700], q_gain=4.0)
     pos = np.arange(C)
     qr = _f64(orc.f64_to_bf16_bits(orc.rope(_f64(q), pos, synth.ROPE_BASE)))
     kr = _f64(orc.f64_to_bf16_bits(orc.rope(_f64(k), pos, synth.ROPE_BASE)))
-    want_rounded = orc.causal_attention(qr, kr, _f64(v), scale, rope_base=None)
+    c_log2 = np.float32(scale) * np.float32(1.4426950408889634)       # fp32, as the launcher forms it
+    q2 = _f64(orc.f64_to_bf16_bits((qr.astype(np.float32) * c_log2).astype(np.float64)))
+    # softmax in base 2 of q2 . kr  ==  softmax in base e of ln(2) q2 . kr
+    want_rounded = orc.causal_attention(q2, kr, _f64(v), float(np.log(2.0)), rope_base=None)
     _check_out(res["out"], want_rounded, "peaky/rounded-rotation")
     want = orc.causal_attention(_f64(q), _f64(k), _f64(v), scale, rope_base=synth.ROPE_BASE)
     err = np.abs(_f64(res["out"]) - want)
