@@ -83,6 +83,7 @@ int kvra_append_kv(const void* k_in, const void* v_in, void* q_inout,
  *   out      [chunk_len, n_q_heads, head_dim] bf16                        (device, write)
  *
  * bf16 MFMA products with fp32 accumulation, fp32 online softmax, P rounded to bf16 before P V.
+ * scale (times log2 e) is multiplied into Q before the score product and that Q rounded to bf16.
  * Errors: KVRA_EINVAL, KVRA_EUNSUPPORTED, KVRA_ELAUNCH.
  */
 int kvra_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
