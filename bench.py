@@ -282,7 +282,7 @@ def main():
     out = torch.empty((C, H, d), dtype=torch.bfloat16, device="cuda")
     stream = torch.cuda.current_stream()
 
-    def run_step(bnds, qw, events=None):
+    def run_step(bnds, qw, events=None, stream=stream):
         for i in range(len(bnds) - 1):
             lo, hi = bnds[i], bnds[i + 1]
             if events is not None:
@@ -357,6 +357,29 @@ def main():
     }
 
     if not args.no_extras:
+        # the same step recorded once into a HIP graph and replayed: what the host-side launch path
+        # and the timing events of the loop above cost (Q is rotated in place again on every replay,
+        # which changes its values but not the work)
+        qg = q_master.clone()
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            run_step(bounds, qg, None, torch.cuda.current_stream())
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        n_rep = max(10, args.steps // 4)
+        g0.record(stream)
+        for _ in range(n_rep):
+            graph.replay()
+        g1.record(stream)
+        torch.cuda.synchronize()
+        graph_ms = g0.elapsed_time(g1) / n_rep
+        result["hip_graph_replay"] = {"ms_per_step": graph_ms, "tflops": flops_step / (graph_ms * 1e-3) / 1e12,
+                                      "replays": n_rep}
+        del graph, qg
+
         # equal-split comparator (KVR-E) and the balancer driven by measured per-chunk times
         reps = 5
         eq = kvra.kvra_equal_split(C, p, 64)
