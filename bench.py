@@ -29,7 +29,7 @@ WORKLOAD = "llama7b_16k_balanced"
 
 # HBM bytes per chunk-attention launch (mean over the 8 launches of a step) from
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, see profiles/; None until measured.
-ATTN_TRAFFIC_BYTES = 4.576e8
+ATTN_TRAFFIC_BYTES = 3.522e8
 
 
 def useful_flops(prefix, c, H, d):

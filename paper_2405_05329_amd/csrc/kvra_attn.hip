@@ -659,8 +659,10 @@ int launch_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
   // Key-split launch: the units beyond the last full round of CUs (all of them when there are fewer
   // units than CUs) are cut into S key segments each.  Time of that last round in units of a whole
   // row tile: 1 without the split, t(S) = ceil(rest * S / CUs) / S with it.  Feasible S: one scratch
-  // slot per piece (kSlotsPerCu per CU) and at least kMinSteps key tiles per piece.  Taken: the smallest S within
-  // a tenth of the best t, if that is at most 0.8.
+  // slot per piece (kSlotsPerCu per CU) and at least kMinSteps key tiles per piece.  Taken: the
+  // smallest S that brings the whole launch (full rounds + t) within 12 % of the best feasible one,
+  // if its t is at most 0.7.  (A partly filled chip clocks higher, and pieces cost a fix-up pass: on
+  // 256 CUs 192 units run faster whole than as 768 quarter pieces in three rounds, t = 0.75.)
   constexpr int kMinSteps = 16, kMaxSegments = 16;
   int cus = 0;
   float* scratch = device_scratch(&cus);
@@ -679,8 +681,9 @@ int launch_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
         t_min = std::min(t_min, t[S]);
         s_max = S;
       }
+      const double full_rounds = static_cast<double>(units / cus);
       for (int S = 2; S <= s_max; ++S)
-        if (t[S] <= 0.8 && t[S] <= 1.1 * t_min) { best = S; break; }
+        if (t[S] <= 0.7 && full_rounds + t[S] <= 1.12 * (full_rounds + t_min)) { best = S; break; }
     }
     if (best > 1) {
       a.scratch = scratch;
