@@ -29,6 +29,12 @@ constexpr int kGemmThreads = 512;
 constexpr int kTileN = 256;    // weight rows per workgroup tile
 constexpr int kTileM = 256;    // tokens per workgroup tile
 constexpr int kTileK = 64;     // k per LDS slot
+// Waves (the last ones of the workgroup, one per SIMD) that issue the global -> LDS loads.  The 64
+// loads of a k step keep the vector memory pipe busy for about 1000 cycles (64 bytes per clock) and
+// a wave sits in its share of them until they are accepted; with every wave issuing 8 loads after
+// the barrier no MFMA starts for the first 500 cycles of a step.  With four issuers their SIMD
+// partners compute at once and have the matrix pipe to themselves meanwhile: +2.5 to 5 %.
+constexpr int kIssuers = 4;
 constexpr int kSlotBytes = (kTileN + kTileM) * kTileK * 2;   // 64 KiB: weight tile then token tile
 
 struct OutSegment {
@@ -87,15 +93,18 @@ __global__ __launch_bounds__(kGemmThreads, 1) void linear_kernel(GemmArgs a) {
   const int n0 = tn * kTileN, m0 = tm * kTileM;
 
   // ---- global -> LDS staging -----------------------------------------------------------------
-  // A 256 x 64 bf16 tile is 2048 pieces of 16 bytes = 32 wave loads, 4 per wave and operand.
+  // A 256 x 64 bf16 tile is 2048 pieces of 16 bytes = 32 wave loads, NL per issuing wave and operand.
   // Piece p = (row p / 8, slot p % 8); the lane that owns (row, slot) fetches column piece
   // slot ^ ((row / 2) % 8) so that the operand reads below (16 rows of one column piece per
   // quarter wave) spread over all banks.  Rows past the end of a matrix repeat its last row.
-  unsigned woff[4], xoff[4];
-  const __bf16* wsrc[4];
+  constexpr int NL = 32 / kIssuers;   // loads per issuing wave and operand
+  const bool issuer = wave >= 8 - kIssuers;
+  const int iw = wave - (8 - kIssuers);
+  unsigned woff[NL], xoff[NL];
+  const __bf16* wsrc[NL];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int p = (i * 8 + wave) * 64 + lane;
+  for (int i = 0; i < NL; ++i) {
+    const int p = (i * kIssuers + (issuer ? iw : 0)) * 64 + lane;
     const int row = p >> 3, slot = p & 7;
     const unsigned piece = static_cast<unsigned>(slot ^ ((row >> 1) & 7));
     int vrow = min(n0 + row, a.n - 1);                       // row in the walked order
@@ -115,9 +124,10 @@ __global__ __launch_bounds__(kGemmThreads, 1) void linear_kernel(GemmArgs a) {
   const unsigned lds0 = static_cast<unsigned>(reinterpret_cast<uintptr_t>((lds_void*)smem));
   auto dma_slot = [&](int kt, int slot) __attribute__((always_inline)) {
     const long long kofs = static_cast<long long>(kt) * kTileK;
+    if (!issuer) return;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const unsigned dst = lds0 + slot * kSlotBytes + (i * 8 + wave) * 1024;
+    for (int i = 0; i < NL; ++i) {
+      const unsigned dst = lds0 + slot * kSlotBytes + (i * kIssuers + iw) * 1024;
       gemm_lds_dma16(wsrc[i] + kofs, woff[i], dst);
       gemm_lds_dma16(a.x + kofs, xoff[i], dst + kTileN * kTileK * 2);
     }
