@@ -92,6 +92,30 @@ int kvra_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
                     float scale, void* out, void* stream);
 
 /*
+ * How kvra_chunk_attn cuts the chunk's trapezoid of (query, key) pairs (Fig. 2(c), Sec. 4.1) into
+ * workgroups on a device with `n_cus` compute units.  Host arithmetic only: nothing is launched or
+ * allocated, and no device needs to be present.  A unit is one kv head x one tile of
+ * `rows_per_tile` query rows (row = token * group + head in group) walked over all the key tiles
+ * it can see; `whole_units` run as one workgroup each; the `split_units` of a partly filled last
+ * round are cut into `segments` equal key ranges, one workgroup each, whose partial results
+ * (`scratch_bytes` of the per-device scratch) a second small kernel merges.  kvra_chunk_attn takes
+ * this plan with the CU count of the current device (and the plain one, segments = 1, if the
+ * scratch could not be allocated).
+ * Errors: KVRA_EINVAL (plan NULL, n_cus < 1, sizes as for kvra_chunk_attn), KVRA_EUNSUPPORTED.
+ */
+typedef struct kvra_attn_plan {
+  int row_tiles;        /* row tiles per kv head */
+  int rows_per_tile;    /* multiple of 32, <= 256 */
+  int key_tile;         /* keys per tile step: 64 at head_dim 128, 128 at head_dim 64 */
+  int whole_units;
+  int split_units;
+  int segments;         /* 1 = no key-split (then split_units = 0) */
+  int64_t scratch_bytes;
+} kvra_attn_plan;
+int kvra_chunk_attn_plan(int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_kv_heads,
+                         int head_dim, int n_cus, kvra_attn_plan* plan);
+
+/*
  * Context-level load balancing (Sec. 4.2), host only.  Picks boundaries 0 = b_0 < b_1 < ... <
  * b_n = context_len, all multiples of `granularity`, that minimise the largest per-chunk cost
  * max_i cost(b_i, b_{i+1} - b_i): with one worker per chunk and many layers the slowest worker

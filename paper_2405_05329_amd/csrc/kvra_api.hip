@@ -62,6 +62,26 @@ extern "C" int kvra_chunk_attn(const void* q, const void* k_cache, const void* v
                                  head_dim, scale, out, static_cast<hipStream_t>(stream));
 }
 
+extern "C" int kvra_chunk_attn_plan(int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_kv_heads,
+                                    int head_dim, int n_cus, kvra_attn_plan* plan) {
+  if (plan == nullptr || n_cus < 1) return KVRA_EINVAL;
+  if (chunk_len < 1 || prefix_len < 0) return KVRA_EINVAL;
+  int rc = check_heads(n_q_heads, n_kv_heads, head_dim);
+  if (rc != KVRA_OK) return rc;
+  if (chunk_len > kMaxTokens || prefix_len > kMaxTokens) return KVRA_EUNSUPPORTED;
+  kvra::AttnPlan p;
+  rc = kvra::plan_chunk_attn(prefix_len, chunk_len, n_q_heads, n_kv_heads, head_dim, n_cus, true, &p);
+  if (rc != KVRA_OK) return rc;
+  plan->row_tiles = p.row_tiles;
+  plan->rows_per_tile = p.rows_per_tile;
+  plan->key_tile = p.key_tile;
+  plan->whole_units = p.whole_units;
+  plan->split_units = p.split_units;
+  plan->segments = p.segments;
+  plan->scratch_bytes = kvra::attn_partial_bytes(head_dim) * p.split_units * p.segments;
+  return KVRA_OK;
+}
+
 // ---------------------------------------------------------------- decoder layer around the attention
 namespace {
 

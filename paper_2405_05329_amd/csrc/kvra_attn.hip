@@ -623,12 +623,71 @@ float* device_scratch(int* cus_out) {
 
 }  // namespace
 
-int launch_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
-                      int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_kv_heads, int head_dim,
-                      float scale, void* out, hipStream_t stream) {
+// Shape of a kvra_chunk_attn launch on a device with `cus` compute units, scratch permitting
+// (host arithmetic only).  Normally one workgroup per unit, every unit whole.  Key-split launch: the
+// units beyond the last full round of CUs (all of them when there are fewer units than CUs) are cut
+// into S key segments each.  Time of that last round in units of a whole row tile: 1 without the
+// split, t(S) = ceil(rest * S / CUs) / S with it.  Feasible S: one scratch slot per piece
+// (kSlotsPerCu per CU) and at least kMinSteps key tiles per piece.  Taken: the smallest S that brings
+// the whole launch (full rounds + t) within 12 % of the best feasible one, if its t is at most 0.7.
+// (A partly filled chip clocks higher, and pieces cost a fix-up pass: on 256 CUs 192 units run
+// faster whole than as 768 quarter pieces in three rounds, t = 0.75.)
+int64_t attn_partial_bytes(int head_dim) {
+  return static_cast<int64_t>(head_dim == 128 ? kPartialFloats(128) : kPartialFloats(64)) * sizeof(float);
+}
+
+int plan_chunk_attn(int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_kv_heads, int head_dim,
+                    int cus, bool scratch_available, AttnPlan* plan) {
   const int G = n_q_heads / n_kv_heads;
   const int64_t vrows = chunk_len * G;
   if (vrows > (int64_t(1) << 30) || prefix_len + chunk_len > (int64_t(1) << 30)) return KVRA_EUNSUPPORTED;
+  // spread the 32-row wave slices evenly over the row tiles (e.g. 34 slices -> 5 tiles of 7)
+  const int64_t slices = (vrows + 31) / 32;
+  const int64_t tiles = (slices + kWaves - 1) / kWaves;
+  const int64_t slices_per_tile = (slices + tiles - 1) / tiles;
+  const int64_t units = tiles * n_kv_heads;
+  if (units > 0x7FFFFFFF) return KVRA_EUNSUPPORTED;
+  plan->row_tiles = static_cast<int>(tiles);
+  plan->rows_per_tile = static_cast<int>(32 * slices_per_tile);
+  plan->key_tile = key_tile(head_dim);
+  plan->whole_units = static_cast<int>(units);
+  plan->split_units = 0;
+  plan->segments = 1;
+  if (!scratch_available || cus <= 0) return KVRA_OK;
+
+  constexpr int kMinSteps = 16, kMaxSegments = 16;
+  const int64_t rest = units % cus;
+  if (rest == 0) return KVRA_OK;
+  // shortest split unit = the last row tile
+  const int64_t last_rows = std::min<int64_t>(plan->rows_per_tile, vrows);
+  const int64_t min_steps = (prefix_len + (last_rows - 1) / G) / plan->key_tile + 1;
+  double t[kMaxSegments + 1], t_min = 1.0;
+  int s_max = 1, best = 1;
+  for (int S = 2; S <= kMaxSegments; ++S) {
+    if (rest * S > kSlotsPerCu * static_cast<int64_t>(cus) || min_steps / S < kMinSteps) break;
+    t[S] = static_cast<double>((rest * S + cus - 1) / cus) / S;
+    t_min = std::min(t_min, t[S]);
+    s_max = S;
+  }
+  const double full_rounds = static_cast<double>(units / cus);
+  for (int S = 2; S <= s_max; ++S)
+    if (t[S] <= 0.7 && full_rounds + t[S] <= 1.12 * (full_rounds + t_min)) { best = S; break; }
+  if (best > 1) {
+    plan->whole_units = static_cast<int>(units - rest);
+    plan->split_units = static_cast<int>(rest);
+    plan->segments = best;
+  }
+  return KVRA_OK;
+}
+
+int launch_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
+                      int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_kv_heads, int head_dim,
+                      float scale, void* out, hipStream_t stream) {
+  int cus = 0;
+  float* scratch = device_scratch(&cus);
+  AttnPlan plan;
+  const int rc0 = plan_chunk_attn(prefix_len, chunk_len, n_q_heads, n_kv_heads, head_dim, cus, scratch != nullptr, &plan);
+  if (rc0 != KVRA_OK) return rc0;
   AttnArgs a;
   a.q = static_cast<const __bf16*>(q);
   a.k = static_cast<const __bf16*>(k_cache);
@@ -638,69 +697,24 @@ int launch_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
   a.chunk = static_cast<int>(chunk_len);
   a.H = n_q_heads;
   a.Hkv = n_kv_heads;
-  a.G = G;
-  // spread the 32-row wave slices evenly over the row tiles (e.g. 34 slices -> 5 tiles of 7)
-  const int64_t slices = (vrows + 31) / 32;
-  const int64_t tiles = (slices + kWaves - 1) / kWaves;
-  const int64_t slices_per_tile = (slices + tiles - 1) / tiles;
-  a.nq_tiles = static_cast<int>(tiles);
-  a.rows_per_wg = static_cast<int>(32 * slices_per_tile);
+  a.G = n_q_heads / n_kv_heads;
+  a.nq_tiles = plan.row_tiles;
+  a.rows_per_wg = plan.rows_per_tile;
   a.c_log2 = scale * 1.4426950408889634f;
-  a.scratch = nullptr;
-  a.n_whole = static_cast<int>(tiles * n_kv_heads);
-  a.n_split = 0;
-  a.segments = 1;
-  const int64_t units = tiles * n_kv_heads;
-  if (units > 0x7FFFFFFF) return KVRA_EUNSUPPORTED;
-  a.bn = key_tile(head_dim);
+  a.bn = plan.key_tile;
+  a.scratch = plan.segments > 1 ? scratch : nullptr;
+  a.n_whole = plan.whole_units;
+  a.n_split = plan.split_units;
+  a.segments = plan.segments;
   const unsigned smem = 2u * kStages * static_cast<unsigned>(a.bn) * static_cast<unsigned>(head_dim) * 2u;   // K ring + V ring
   const dim3 b3(kThreads);
-
-  // Key-split launch: the units beyond the last full round of CUs (all of them when there are fewer
-  // units than CUs) are cut into S key segments each.  Time of that last round in units of a whole
-  // row tile: 1 without the split, t(S) = ceil(rest * S / CUs) / S with it.  Feasible S: one scratch
-  // slot per piece (kSlotsPerCu per CU) and at least kMinSteps key tiles per piece.  Taken: the
-  // smallest S that brings the whole launch (full rounds + t) within 12 % of the best feasible one,
-  // if its t is at most 0.7.  (A partly filled chip clocks higher, and pieces cost a fix-up pass: on
-  // 256 CUs 192 units run faster whole than as 768 quarter pieces in three rounds, t = 0.75.)
-  constexpr int kMinSteps = 16, kMaxSegments = 16;
-  int cus = 0;
-  float* scratch = device_scratch(&cus);
-  if (scratch != nullptr && cus > 0) {
-    const int64_t rest = units % cus;
-    // shortest split unit = the last row tile
-    const int64_t last_rows = std::min<int64_t>(a.rows_per_wg, vrows);
-    const int64_t min_steps = (prefix_len + (last_rows - 1) / G) / a.bn + 1;
-    int best = 1;
-    if (rest > 0) {
-      double t[kMaxSegments + 1], t_min = 1.0;
-      int s_max = 1;
-      for (int S = 2; S <= kMaxSegments; ++S) {
-        if (rest * S > kSlotsPerCu * static_cast<int64_t>(cus) || min_steps / S < kMinSteps) break;
-        t[S] = static_cast<double>((rest * S + cus - 1) / cus) / S;
-        t_min = std::min(t_min, t[S]);
-        s_max = S;
-      }
-      const double full_rounds = static_cast<double>(units / cus);
-      for (int S = 2; S <= s_max; ++S)
-        if (t[S] <= 0.7 && full_rounds + t[S] <= 1.12 * (full_rounds + t_min)) { best = S; break; }
-    }
-    if (best > 1) {
-      a.scratch = scratch;
-      a.n_whole = static_cast<int>(units - rest);
-      a.n_split = static_cast<int>(rest);
-      a.segments = best;
-      const dim3 g_main(static_cast<unsigned>(a.n_whole + rest * best)), g_fix(static_cast<unsigned>(rest * kWaves * (head_dim / 32)));
-      int rc = head_dim == 128 ? launch_kernel(chunk_attn_kernel<128>, g_main, b3, a, stream, smem)
-                               : launch_kernel(chunk_attn_kernel<64>, g_main, b3, a, stream, smem);
-      if (rc != KVRA_OK) return rc;
-      return head_dim == 128 ? launch_kernel(chunk_attn_fixup_kernel<128>, g_fix, dim3(64), a, stream)
-                             : launch_kernel(chunk_attn_fixup_kernel<64>, g_fix, dim3(64), a, stream);
-    }
-  }
-  const dim3 g3(static_cast<unsigned>(units));
-  if (head_dim == 128) return launch_kernel(chunk_attn_kernel<128>, g3, b3, a, stream, smem);
-  return launch_kernel(chunk_attn_kernel<64>, g3, b3, a, stream, smem);
+  const dim3 g_main(static_cast<unsigned>(a.n_whole + static_cast<int64_t>(a.n_split) * a.segments));
+  const int rc = head_dim == 128 ? launch_kernel(chunk_attn_kernel<128>, g_main, b3, a, stream, smem)
+                                 : launch_kernel(chunk_attn_kernel<64>, g_main, b3, a, stream, smem);
+  if (rc != KVRA_OK || a.segments == 1) return rc;
+  const dim3 g_fix(static_cast<unsigned>(a.n_split * kWaves * (head_dim / 32)));
+  return head_dim == 128 ? launch_kernel(chunk_attn_fixup_kernel<128>, g_fix, dim3(64), a, stream)
+                         : launch_kernel(chunk_attn_fixup_kernel<64>, g_fix, dim3(64), a, stream);
 }
 
 }  // namespace kvra

@@ -19,6 +19,19 @@ int launch_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
                       int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_kv_heads, int head_dim,
                       float scale, void* out, hipStream_t stream);
 
+// Launch shape of kvra_chunk_attn for a device with `cus` compute units (pure host arithmetic).
+struct AttnPlan {
+  int row_tiles;       // row tiles per kv head
+  int rows_per_tile;   // virtual rows (token * group + head in group) per workgroup, <= 256
+  int key_tile;        // keys per tile step
+  int whole_units;     // (kv head, row tile) units that run as one workgroup
+  int split_units;     // units cut into `segments` key segments, one workgroup each, merged by the fix-up kernel
+  int segments;        // 1 = no key-split
+};
+int64_t attn_partial_bytes(int head_dim);   // scratch bytes per (split unit, key segment)
+int plan_chunk_attn(int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_kv_heads, int head_dim,
+                    int cus, bool scratch_available, AttnPlan* plan);
+
 // out[m, n_out] = x[m, k] . w[n_out, k]^T (+ residual), or silu(x . w^T) * (x . w2^T) when w2 is given.
 // The n_out output columns are split over n_seg (1..3) dense matrices of seg_cols[s] columns each.
 int launch_linear(const void* x, const void* w, const void* w2, const void* residual,

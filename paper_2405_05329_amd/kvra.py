@@ -29,6 +29,13 @@ class KvraError(RuntimeError):
         super().__init__(f"{where}: {kvra_strerror(code)} ({code})")
 
 
+class KvraAttnPlan(ctypes.Structure):
+    """Mirror of `kvra_attn_plan` in include/kvra.h."""
+    _fields_ = [("row_tiles", ctypes.c_int), ("rows_per_tile", ctypes.c_int), ("key_tile", ctypes.c_int),
+                ("whole_units", ctypes.c_int), ("split_units", ctypes.c_int), ("segments", ctypes.c_int),
+                ("scratch_bytes", ctypes.c_int64)]
+
+
 def _load() -> ctypes.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(
@@ -48,6 +55,8 @@ def _load() -> ctypes.CDLL:
     lib.kvra_append_kv.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, f32, vp]
     lib.kvra_chunk_attn.restype = i32
     lib.kvra_chunk_attn.argtypes = [vp, vp, vp, i64, i64, i32, i32, i32, f32, vp, vp]
+    lib.kvra_chunk_attn_plan.restype = i32
+    lib.kvra_chunk_attn_plan.argtypes = [i64, i64, i32, i32, i32, i32, ctypes.POINTER(KvraAttnPlan)]
     lib.kvra_balance.restype = i32
     lib.kvra_balance.argtypes = [i64, i32, i64, ctypes.c_void_p, vp, ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)]
     lib.kvra_equal_split.restype = i32
@@ -144,6 +153,15 @@ def kvra_chunk_attn(q, k_cache, v_cache, prefix_len, chunk_len, n_q_heads, n_kv_
     if check and rc != KVRA_OK:
         raise KvraError(rc, "kvra_chunk_attn")
     return rc
+
+
+def kvra_chunk_attn_plan(prefix_len, chunk_len, n_q_heads, n_kv_heads, head_dim, n_cus) -> dict:
+    plan = KvraAttnPlan()
+    rc = _lib.kvra_chunk_attn_plan(prefix_len, chunk_len, n_q_heads, n_kv_heads, head_dim, n_cus,
+                                   ctypes.byref(plan))
+    if rc != 0:
+        raise KvraError(rc, "kvra_chunk_attn_plan")
+    return {name: getattr(plan, name) for name, _ in KvraAttnPlan._fields_}
 
 
 def kvra_balance(context_len, n_chunks, granularity, cost=None):

@@ -284,3 +284,66 @@ def test_layer_and_linear_reject_bad_arguments_before_any_launch():
         kvra.kvra_rms_norm(p, p, p, 4, 100, 1e-6)                             # hidden not a multiple of 8
     with pytest.raises(kvra.KvraError):
         kvra.kvra_rms_norm(p, None, p, 4, 64, 1e-6)
+
+
+# ------------------------------------------------------------------ launch plan of kvra_chunk_attn
+def test_attention_launch_plan_of_the_16k_workload():
+    """Llama-7B shape, 8 balanced chunks, 256 compute units: which chunks run whole and which have
+    the units of their last round of CUs cut into key segments."""
+    H, d, cus = 32, 128, 256
+    want = {  # (prefix, chunk): (row tiles, rows per tile, whole units, split units, segments)
+        (0, 5824): (23, 256, 736, 0, 1),          # 224 units in the last round: no S gets it below 0.7
+        (5824, 2368): (10, 256, 256, 64, 3),      # 320 units: one full round, 64 units in thirds
+        (8192, 1856): (8, 256, 256, 0, 1),        # exactly one round
+        (10048, 1536): (6, 256, 192, 0, 1),       # 192 units: quarter pieces would need 3 rounds (0.75)
+        (11584, 1344): (6, 224, 192, 0, 1),
+        (12928, 1280): (5, 256, 0, 160, 3),       # 160 units in thirds: 480 pieces, two rounds (0.67)
+        (14208, 1088): (5, 224, 0, 160, 3),
+        (15296, 1088): (5, 224, 0, 160, 3),
+    }
+    for (prefix, c), (tiles, rows, whole, split, seg) in want.items():
+        p = kvra.kvra_chunk_attn_plan(prefix, c, H, H, d, cus)
+        assert (p["row_tiles"], p["rows_per_tile"], p["whole_units"], p["split_units"], p["segments"]) == \
+            (tiles, rows, whole, split, seg), (prefix, c, p)
+        assert p["key_tile"] == 64
+
+
+def test_attention_launch_plan_invariants_and_decode_like_shapes():
+    # a few tokens behind a long prefix: one unit per head, cut as finely as the round allows
+    p = kvra.kvra_chunk_attn_plan(20000, 8, 32, 32, 128, 256)
+    assert (p["row_tiles"], p["rows_per_tile"], p["whole_units"], p["split_units"], p["segments"]) == (1, 32, 0, 32, 8)
+    # too few keys for 16 key tiles per piece: whole
+    p = kvra.kvra_chunk_attn_plan(100, 8, 32, 32, 128, 256)
+    assert (p["split_units"], p["segments"], p["scratch_bytes"]) == (0, 1, 0)
+    # grouped queries fold into the row index; head_dim 64 walks 128-key tiles
+    p = kvra.kvra_chunk_attn_plan(0, 4096, 71, 1, 64, 256)
+    assert p["key_tile"] == 128 and p["row_tiles"] == (4096 * 71 + 255) // 256
+    rng = random.Random(5)
+    for _ in range(300):
+        H, Hkv, d = rng.choice([(32, 32, 128), (32, 8, 128), (32, 1, 128), (71, 1, 64), (16, 16, 64)])
+        prefix, c = rng.choice([0, 1, 63, 4096, 30000]), rng.choice([1, 7, 64, 300, 1088, 5000])
+        cus = rng.choice([8, 64, 256, 304])
+        p = kvra.kvra_chunk_attn_plan(prefix, c, H, Hkv, d, cus)
+        rows = c * (H // Hkv)
+        assert p["rows_per_tile"] % 32 == 0 and 32 <= p["rows_per_tile"] <= 256
+        assert p["row_tiles"] * p["rows_per_tile"] >= rows > (p["row_tiles"] - 1) * p["rows_per_tile"]
+        assert p["whole_units"] + p["split_units"] == p["row_tiles"] * Hkv
+        assert (p["segments"] == 1) == (p["split_units"] == 0)
+        assert p["whole_units"] % cus == 0 or p["split_units"] == 0
+        assert p["split_units"] * p["segments"] <= 3 * cus                  # scratch slots
+        assert p["scratch_bytes"] == (p["split_units"] * p["segments"] * 8 * (d // 32 * 16 + 2) * 64 * 4
+                                      if p["split_units"] else 0)
+        if p["segments"] > 1:                                               # at least 16 key tiles per piece
+            last_rows = min(p["rows_per_tile"], rows)
+            assert ((prefix + (last_rows - 1) // (H // Hkv)) // p["key_tile"] + 1) // p["segments"] >= 16
+
+
+def test_attention_launch_plan_rejects_bad_arguments():
+    with pytest.raises(kvra.KvraError):
+        kvra.kvra_chunk_attn_plan(0, 0, 4, 4, 64, 256)
+    with pytest.raises(kvra.KvraError):
+        kvra.kvra_chunk_attn_plan(0, 8, 4, 3, 64, 256)
+    with pytest.raises(kvra.KvraError):
+        kvra.kvra_chunk_attn_plan(0, 8, 4, 4, 96, 256)
+    with pytest.raises(kvra.KvraError):
+        kvra.kvra_chunk_attn_plan(0, 8, 4, 4, 64, 0)
