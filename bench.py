@@ -384,6 +384,7 @@ def main():
         reps = 5
         eq = kvra.kvra_equal_split(C, p, 64)
         tot = np.zeros(p)
+        eq_append = np.zeros(p)
         for rep in range(reps + 1):
             qw = q_work[rep % n_buf]
             qw.copy_(q_master)
@@ -392,8 +393,19 @@ def main():
             torch.cuda.synchronize()
             if rep:
                 tot += np.array([x[0].elapsed_time(x[2]) for x in e])
+                eq_append += np.array([x[0].elapsed_time(x[1]) for x in e])
         result["makespan"]["equal_split_ms"] = float((tot / reps).max())
         result["makespan"]["equal_split_boundaries"] = eq
+
+        # the same per-chunk times in the chain of processes (one per chunk, 32 layers, every layer
+        # waiting for the precedent's cache; no transfer time: one GPU measures none)
+        def chain_ms(bnds, append_ms, attn_ms):
+            a = {bnds[i]: float(append_ms[i]) for i in range(p)}
+            t = {bnds[i]: float(attn_ms[i]) for i in range(p)}
+            return kvra.kvra_chain_ttft(bnds, 32, lambda pre, c: a[pre], lambda pre, c: t[pre])
+        result["makespan"]["chain_ttft_32_layers_ms"] = {
+            "balanced": chain_ms(bounds, append_mean, attn_mean),
+            "equal_split": chain_ms(eq, eq_append / reps, (tot - eq_append) / reps)}
 
         # measured cost table t(prefix, c) on a coarse grid, bilinear in between, fed to kvra_balance
         grid = [1024 * i for i in range(0, C // 1024 + 1)]

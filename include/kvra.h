@@ -147,6 +147,23 @@ int kvra_makespan(const int64_t* boundaries, int n_chunks, kvra_cost_fn cost, vo
                   double* makespan_out);
 
 /*
+ * Time to first token of the chain of processes p_0 -> p_1 -> ... (Sec. 4 overview and Fig. 5(b):
+ * every process runs every layer on its own chunk and must wait, in each layer, for the KV-cache of
+ * its precedent, which makes the later processes lag by layers), with one process per chunk and
+ * `n_layers` identical layers.  Per layer, process i first spends before_attn(prefix_i, c_i) (norm,
+ * projections, rotation, append); its cache is complete when that is done and the cache of process
+ * i-1 has arrived, handoff(prefix_{i-1}, c_{i-1}) after that one was complete (NULL: no transfer
+ * time); then it attends for attn(prefix_i, c_i) plus whatever follows in the layer, and starts
+ * the next layer.  The result is the time at which the last process leaves the last layer.
+ * Host only.  All three callbacks get the same `user`; costs must be >= 0.
+ * Errors (KVRA_EINVAL): NULL boundaries / ttft_out / before_attn / attn, n_chunks < 1,
+ * n_layers < 1, boundaries not strictly rising from 0, a negative or NaN cost.
+ */
+int kvra_chain_ttft(const int64_t* boundaries, int n_chunks, int n_layers,
+                    kvra_cost_fn before_attn, kvra_cost_fn attn, kvra_cost_fn handoff,
+                    void* user, double* ttft_out);
+
+/*
  * One-dimensional search for two processes (Sec. 4.2, the two-partition panel of the search
  * figure): the first process's cost grows and the second's shrinks as the interior boundary moves
  * right, so the crossing is found by bisection in O(log(context_len/granularity)) cost

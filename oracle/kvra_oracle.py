@@ -17,14 +17,15 @@ What it defines
   * the context-level load-balancing objective of Sec. 4.2 reduced to per-chunk costs:
     makespan of a partition, even split, exhaustive search; and its search tools: the
     one-dimensional scan for two processes, the hierarchical grid search, the lookup table
-    with linear interpolation;
+    with linear interpolation; and the time to first token of the chain of processes when
+    every layer waits for the precedent's cache (Sec. 4 overview, Fig. 5(b));
   * the decoder layer a process runs around the attention block (App. C listing: q/k/v and
     output projections; RMSNorm and the SwiGLU MLP come from the LLaMA models of Sec. 5),
     exact or with bf16 storage rounding of every intermediate tensor.
 
 Pinned by tests/test_oracle_*.py against hand-computed rationals, closed forms,
 torch's CPU scaled_dot_product_attention / rms_norm / silu / linear, the paper's worked
-9-token example, its search example and brute force.  Parity status: the rotary pairing convention (half-split versus
+9-token example, its search example, brute force and (chain timing) closed forms.  Parity status: the rotary pairing convention (half-split versus
 interleaved) is unpinned by the paper; everything else is pinned.
 """
 from __future__ import annotations
@@ -299,6 +300,28 @@ def makespan(boundaries, cost=analytic_cost):
     layers, the slowest worker sets the pace (Sec. 4.2, second bullet)."""
     b = [int(x) for x in boundaries]
     return max(cost(b[i], b[i + 1] - b[i]) for i in range(len(b) - 1))
+
+
+def chain_ttft(boundaries, n_layers, before_attn, attn, handoff=None):
+    """Time to first token of the chain p_0 -> p_1 -> ... with one process per chunk (Sec. 4
+    overview; Fig. 5(b), layer misalignment): in every layer a process first does its own work up
+    to the cache append (`before_attn`), can attend only once the cache of its precedent has
+    arrived as well (`handoff` after that cache was complete), attends (`attn`) and moves on to
+    the next layer.  Written as the event times of every (process, layer), nothing folded."""
+    b = [int(x) for x in boundaries]
+    p = len(b) - 1
+    cache = [[0.0] * n_layers for _ in range(p)]   # own K,V appended and all earlier rows present
+    done = [[0.0] * n_layers for _ in range(p)]    # process leaves the layer
+    for layer in range(n_layers):
+        for i in range(p):
+            start = done[i][layer - 1] if layer > 0 else 0.0
+            own = start + before_attn(b[i], b[i + 1] - b[i])
+            if i > 0:
+                sent = handoff(b[i - 1], b[i] - b[i - 1]) if handoff is not None else 0.0
+                own = max(own, cache[i - 1][layer] + sent)
+            cache[i][layer] = own
+            done[i][layer] = own + attn(b[i], b[i + 1] - b[i])
+    return done[p - 1][n_layers - 1]
 
 
 def equal_split(context_len, p, granularity):

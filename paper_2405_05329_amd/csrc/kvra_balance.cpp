@@ -4,6 +4,7 @@
 // model), so an exact dynamic programme over the grid is affordable.
 #include "kvra.h"
 
+#include <algorithm>
 #include <cmath>
 #include <limits>
 #include <vector>
@@ -115,3 +116,42 @@ extern "C" int kvra_makespan(const int64_t* boundaries, int n_chunks, kvra_cost_
   *makespan_out = worst;
   return KVRA_OK;
 }
+
+// Time to first token of the process chain (Sec. 4, overview: each process runs every layer on its
+// chunk and waits, per layer, for the KV-cache of its precedent; Fig. 5(b) shows the resulting
+// layer misalignment).  Per layer l and process i:
+//   cache(i, l)  = max(start(i, l) + before(i), cache(i-1, l) + handoff(i-1))   own K,V appended and
+//                                                                               everything earlier arrived
+//   done(i, l)   = cache(i, l) + attend(i)
+//   start(i, l+1) = done(i, l)
+// and the token comes out of the last process after the last layer: done(p-1, L-1).
+extern "C" int kvra_chain_ttft(const int64_t* boundaries, int n_chunks, int n_layers,
+                               kvra_cost_fn before_attn, kvra_cost_fn attn, kvra_cost_fn handoff,
+                               void* user, double* ttft_out) {
+  if (boundaries == nullptr || ttft_out == nullptr || n_chunks < 1 || n_layers < 1) return KVRA_EINVAL;
+  if (before_attn == nullptr || attn == nullptr) return KVRA_EINVAL;
+  if (boundaries[0] != 0) return KVRA_EINVAL;
+  std::vector<double> a(n_chunks), t(n_chunks), x(n_chunks, 0.0), start(n_chunks, 0.0);
+  for (int i = 0; i < n_chunks; ++i) {
+    const int64_t c = boundaries[i + 1] - boundaries[i];
+    if (c < 1) return KVRA_EINVAL;
+    a[i] = before_attn(boundaries[i], c, user);
+    t[i] = attn(boundaries[i], c, user);
+    if (handoff != nullptr && i + 1 < n_chunks) x[i] = handoff(boundaries[i], c, user);
+    if (std::isnan(a[i]) || std::isnan(t[i]) || std::isnan(x[i]) || a[i] < 0 || t[i] < 0 || x[i] < 0) return KVRA_EINVAL;
+  }
+  double done_last = 0.0;
+  for (int l = 0; l < n_layers; ++l) {
+    double arrived = 0.0;   // cache(i-1, l) + handoff(i-1); nothing to wait for at i = 0
+    for (int i = 0; i < n_chunks; ++i) {
+      const double cache = std::max(start[i] + a[i], arrived);
+      const double done = cache + t[i];
+      arrived = cache + x[i];
+      start[i] = done;
+      done_last = done;
+    }
+  }
+  *ttft_out = done_last;
+  return KVRA_OK;
+}
+

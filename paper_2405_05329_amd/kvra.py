@@ -61,6 +61,9 @@ def _load() -> ctypes.CDLL:
     lib.kvra_balance.argtypes = [i64, i32, i64, ctypes.c_void_p, vp, ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)]
     lib.kvra_equal_split.restype = i32
     lib.kvra_equal_split.argtypes = [i64, i32, i64, ctypes.POINTER(i64)]
+    lib.kvra_chain_ttft.restype = i32
+    lib.kvra_chain_ttft.argtypes = [ctypes.POINTER(i64), i32, i32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                    vp, ctypes.POINTER(ctypes.c_double)]
     lib.kvra_makespan.restype = i32
     lib.kvra_makespan.argtypes = [ctypes.POINTER(i64), i32, ctypes.c_void_p, vp, ctypes.POINTER(ctypes.c_double)]
     pi64, pf64 = ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)
@@ -195,6 +198,19 @@ def kvra_makespan(boundaries, cost=None) -> float:
     if rc != KVRA_OK:
         raise KvraError(rc, "kvra_makespan")
     return mk.value
+
+
+def kvra_chain_ttft(boundaries, n_layers, before_attn, attn, handoff=None) -> float:
+    b = [int(x) for x in boundaries]
+    arr = (ctypes.c_int64 * len(b))(*b)
+    out = ctypes.c_double()
+    cb_a, p_a = _cost(before_attn)
+    cb_t, p_t = _cost(attn)
+    cb_x, p_x = _cost(handoff)
+    rc = _lib.kvra_chain_ttft(arr, len(b) - 1, n_layers, p_a, p_t, p_x, None, ctypes.byref(out))
+    if rc != KVRA_OK:
+        raise KvraError(rc, "kvra_chain_ttft")
+    return out.value
 
 
 def _i64_array(values):
