@@ -410,19 +410,23 @@ def main():
         # measured cost table t(prefix, c) on a coarse grid, bilinear in between, fed to kvra_balance
         grid = [1024 * i for i in range(0, C // 1024 + 1)]
         table = {}
+        append_table = {}
         qw = q_work[0]
         def measure(prefix, c):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            best = float("inf")
+            e0, em, e1 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+            best, best_append = float("inf"), float("inf")
             for _ in range(3):
                 e0.record(stream)
                 kvra.kvra_append_kv(k_in[prefix:prefix + c], v_in[prefix:prefix + c], qw[prefix:prefix + c], k_cache,
                                     v_cache, prefix, c, C, H, Hkv, d, synth.ROPE_BASE, stream=stream)
+                em.record(stream)
                 kvra.kvra_chunk_attn(qw[prefix:prefix + c], k_cache, v_cache, prefix, c, H, Hkv, d, scale,
                                      out[prefix:prefix + c], stream=stream)
                 e1.record(stream)
                 torch.cuda.synchronize()
                 best = min(best, e0.elapsed_time(e1))
+                best_append = min(best_append, e0.elapsed_time(em))
+            append_table[(prefix, c)] = best_append
             return best
         cs = [256, 512, 1024, 2048, 3072, 4096, 6144, 8192]
         ps = [0, 2048, 4096, 8192, 12288, 15360]
@@ -476,6 +480,36 @@ def main():
                                 "measured_ms": measured_makespan(gs_b)},
             "seeded": {"boundaries": gs2_b, "predicted_ms": gs2_m, "cost_evaluations": gs2_ev,
                        "measured_ms": measured_makespan(gs2_b)}}
+        # the search on the paper's own objective, the time to first token of the chain (32 layers, no
+        # transfer time), with the append and the attention fitted separately; seeded with kvra_balance's
+        # partition, whose objective is the per-layer makespan
+        ya = np.array([append_table[k] for k in table])
+        ca, *_ = np.linalg.lstsq(np.array([[1.0, c] for (_, c) in table]), ya, rcond=None)
+        ct, *_ = np.linalg.lstsq(A, y - ya, rcond=None)
+        def ttft_ms(bnds):
+            cache_prev = [0.0] * 32
+            start = 0.0
+            for i in range(len(bnds) - 1):
+                pre, c = bnds[i], bnds[i + 1] - bnds[i]
+                a_i = ca[0] + ca[1] * c
+                t_i = ct[0] + ct[1] * c + ct[2] * c * (2 * pre + c)
+                start = 0.0
+                for layer in range(32):
+                    cache = max(start + a_i, cache_prev[layer])
+                    cache_prev[layer] = cache
+                    start = cache + t_i
+            return start
+        t0 = time.perf_counter()
+        ts_b, ts_v, ts_ev = kvra.kvra_search_grid_objective(C, p, 64, ttft_ms, start=bal)
+        result["makespan"]["grid_search_on_chain_ttft"] = {
+            "boundaries": ts_b, "predicted_ttft_ms": ts_v, "objective_evaluations": ts_ev,
+            "host_s": time.perf_counter() - t0,
+            "predicted_ttft_ms_of_kvra_balance": ttft_ms(bal),
+            "predicted_ttft_ms_of_even_split": ttft_ms(eq),
+            "check_against_kvra_chain_ttft": kvra.kvra_chain_ttft(
+                ts_b, 32, lambda pre, c: float(ca[0] + ca[1] * c),
+                lambda pre, c: float(ct[0] + ct[1] * c + ct[2] * c * (2 * pre + c)))}
+
         # lookup table at 4k spacing and predicted partitionings (KVR-P) for lengths between entries,
         # against the partitioning searched at that length (KVR-S) and the even split (KVR-E)
         if C >= 16384:

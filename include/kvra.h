@@ -196,6 +196,22 @@ int kvra_search_grid(int64_t context_len, int n_chunks, int64_t granularity, con
                      int64_t* evaluations_out);
 
 /*
+ * The hierarchical grid search with the objective left to the caller, as in the paper, whose search
+ * runs on the measured time to first token of the whole chain (Sec. 4.2): same levels, strides,
+ * candidates and tie-break as kvra_search_grid, but `objective` is called once per feasible
+ * combination (up to 5^(n_chunks-1) per level; n_chunks <= 10) with a host array of n_chunks + 1
+ * boundaries.  kvra_chain_ttft over fitted per-chunk costs is one such objective.
+ *   value_out, evaluations_out   host scalars or NULL
+ * Errors: KVRA_EINVAL as kvra_search_grid, NULL objective, an objective that returns NaN;
+ * KVRA_EUNSUPPORTED for n_chunks > 10.
+ */
+typedef double (*kvra_partition_fn)(const int64_t* boundaries, int n_chunks, void* user);
+
+int kvra_search_grid_objective(int64_t context_len, int n_chunks, int64_t granularity, const int64_t* start,
+                               kvra_partition_fn objective, void* user, int64_t* boundaries_out,
+                               double* value_out, int64_t* evaluations_out);
+
+/*
  * Predicted partitioning from two lookup-table entries (KVR-P; Sec. 4.2, and the partitioning
  * paragraph of Sec. 5 that interpolates 8k and 12k entries for a 10k context).  The cumulative
  * ratios b_k / length of the two entries are blended linearly in context_len (clamped to the

@@ -389,7 +389,7 @@ def grid_search_strides(context_len, p, granularity):
     return out
 
 
-def hierarchical_grid_search(context_len, p, granularity, cost=analytic_cost, start=None):
+def hierarchical_grid_search(context_len, p, granularity, cost=analytic_cost, start=None, objective=None):
     """Hierarchical grid search of Sec. 4.2 (Fig. 6(b-d); cost model in the appendix on lookup
     table generation: five values per interior boundary and level).
 
@@ -399,12 +399,16 @@ def hierarchical_grid_search(context_len, p, granularity, cost=analytic_cost, st
     lexicographically smallest boundary vector) becomes the centre of the next level, whose
     stride is half as large, so the next level scans exactly +-1 old stride around it.
     Starts from the even split unless `start` is given.  Returns (boundaries, makespan, levels)
-    where levels is the list of (stride, centre after the level).
+    where levels is the list of (stride, centre after the level).  With `objective` (a function
+    of the boundary list) that value is minimised instead of the makespan of `cost`: the paper
+    searches on the time to first token.
     """
+    if objective is None:
+        objective = lambda b: makespan(b, cost)
     cur = list(start) if start is not None else equal_split(context_len, p, granularity)
     assert cur[0] == 0 and cur[-1] == context_len and len(cur) == p + 1
     levels = []
-    best_m = makespan(cur, cost)
+    best_m = objective(cur)
     for stride in grid_search_strides(context_len, p, granularity):
         axes = [[cur[k] + o * stride for o in (-2, -1, 0, 1, 2)] for k in range(1, p)]
         best, best_b = None, None
@@ -412,7 +416,7 @@ def hierarchical_grid_search(context_len, p, granularity, cost=analytic_cost, st
             b = [0] + list(inner) + [context_len]
             if any(b[i + 1] <= b[i] for i in range(p)):
                 continue
-            m = makespan(b, cost)
+            m = objective(b)
             if best is None or m < best or (m == best and b < best_b):
                 best, best_b = m, b
         cur, best_m = best_b, best

@@ -149,6 +149,69 @@ extern "C" int kvra_search_grid(int64_t context_len, int n_chunks, int64_t granu
   return KVRA_OK;
 }
 
+// The same search with the objective left to the caller (the paper searches on the measured time to
+// first token of the whole chain): no structure to exploit, so every level walks all the
+// 5^(n_chunks-1) combinations in lexicographic order and keeps the first best one.
+extern "C" int kvra_search_grid_objective(int64_t context_len, int n_chunks, int64_t granularity,
+                                          const int64_t* start, kvra_partition_fn objective, void* user,
+                                          int64_t* boundaries_out, double* value_out, int64_t* evaluations_out) {
+  if (boundaries_out == nullptr || objective == nullptr || !grid_ok(context_len, n_chunks, granularity)) return KVRA_EINVAL;
+  if (n_chunks > 10) return KVRA_EUNSUPPORTED;   // 5^9 combinations per level is the most this walks
+  const int p = n_chunks;
+  const int64_t g = granularity;
+  std::vector<int64_t> cur(p + 1);
+  if (start != nullptr) {
+    if (!partition_ok(start, p, context_len, g)) return KVRA_EINVAL;
+    for (int k = 0; k <= p; ++k) cur[k] = start[k];
+  } else {
+    int rc = kvra_equal_split(context_len, p, g, cur.data());
+    if (rc != KVRA_OK) return rc;
+  }
+  int64_t evals = 0;
+  double best = objective(cur.data(), p, user);
+  ++evals;
+  if (std::isnan(best)) return KVRA_EINVAL;
+
+  int64_t stride = g;
+  while (2 * (2 * stride) * static_cast<int64_t>(p) < context_len) stride *= 2;
+  std::vector<int64_t> b(p + 1), best_b(p + 1);
+  std::vector<int> off(p + 1);
+  for (; stride >= g; stride /= 2) {
+    bool have = false;
+    double level_best = 0.0;
+    for (int k = 1; k < p; ++k) off[k] = 0;
+    b[0] = 0;
+    b[p] = context_len;
+    for (;;) {
+      // offsets off[k] in 0..4 stand for -2..2 strides; the first axis is the slowest digit, so the
+      // walk is in lexicographic order of the boundary vectors
+      bool ok = true;
+      for (int k = 1; k < p; ++k) {
+        b[k] = cur[k] + (off[k] - 2) * stride;
+        if (b[k] <= b[k - 1]) { ok = false; break; }
+      }
+      if (ok && b[p] <= b[p - 1]) ok = false;
+      if (ok) {
+        const double v = objective(b.data(), p, user);
+        ++evals;
+        if (std::isnan(v)) return KVRA_EINVAL;
+        if (!have || v < level_best) { have = true; level_best = v; best_b = b; }
+      }
+      int k = p - 1;
+      while (k >= 1 && off[k] == 4) { off[k] = 0; --k; }
+      if (k < 1) break;
+      ++off[k];
+    }
+    if (!have) return KVRA_EINVAL;   // cannot happen: the centre itself is feasible
+    cur = best_b;
+    best = level_best;
+  }
+  for (int k = 0; k <= p; ++k) boundaries_out[k] = cur[k];
+  if (value_out != nullptr) *value_out = best;
+  if (evaluations_out != nullptr) *evaluations_out = evals;
+  return KVRA_OK;
+}
+
 extern "C" int kvra_interpolate(int64_t context_len, int n_chunks, int64_t granularity,
                                 int64_t len_lo, const int64_t* bounds_lo,
                                 int64_t len_hi, const int64_t* bounds_hi, int64_t* boundaries_out) {

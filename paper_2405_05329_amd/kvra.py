@@ -71,6 +71,8 @@ def _load() -> ctypes.CDLL:
     lib.kvra_search_two_way.argtypes = [i64, i64, ctypes.c_void_p, vp, pi64, pf64, pi64]
     lib.kvra_search_grid.restype = i32
     lib.kvra_search_grid.argtypes = [i64, i32, i64, pi64, ctypes.c_void_p, vp, pi64, pf64, pi64]
+    lib.kvra_search_grid_objective.restype = i32
+    lib.kvra_search_grid_objective.argtypes = [i64, i32, i64, pi64, ctypes.c_void_p, vp, pi64, pf64, pi64]
     lib.kvra_interpolate.restype = i32
     lib.kvra_interpolate.argtypes = [i64, i32, i64, i64, pi64, i64, pi64, pi64]
     lib.kvra_table_predict.restype = i32
@@ -247,6 +249,23 @@ def kvra_search_grid(context_len, n_chunks, granularity, cost=None, start=None):
     if rc != KVRA_OK:
         raise KvraError(rc, "kvra_search_grid")
     return list(out), mk.value, ev.value
+
+
+PARTITION_FN = ctypes.CFUNCTYPE(ctypes.c_double, ctypes.POINTER(ctypes.c_int64), ctypes.c_int, ctypes.c_void_p)
+
+
+def kvra_search_grid_objective(context_len, n_chunks, granularity, objective, start=None):
+    """objective(list of n_chunks + 1 boundaries) -> float.  Returns (boundaries, value, evaluations)."""
+    cb = PARTITION_FN(lambda bptr, n, _user: float(objective([bptr[k] for k in range(n + 1)])))
+    out = (ctypes.c_int64 * (n_chunks + 1))()
+    val = ctypes.c_double()
+    ev = ctypes.c_int64()
+    st = _i64_array(start) if start is not None else None
+    rc = _lib.kvra_search_grid_objective(context_len, n_chunks, granularity, st, ctypes.cast(cb, ctypes.c_void_p), None,
+                                         out, ctypes.byref(val), ctypes.byref(ev))
+    if rc != KVRA_OK:
+        raise KvraError(rc, "kvra_search_grid_objective")
+    return list(out), val.value, ev.value
 
 
 def kvra_interpolate(context_len, granularity, len_lo, bounds_lo, len_hi, bounds_hi):

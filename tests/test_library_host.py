@@ -347,3 +347,51 @@ def test_attention_launch_plan_rejects_bad_arguments():
         kvra.kvra_chunk_attn_plan(0, 8, 4, 4, 96, 256)
     with pytest.raises(kvra.KvraError):
         kvra.kvra_chunk_attn_plan(0, 8, 4, 4, 64, 0)
+
+
+# ------------------------------------------------------------------ grid search on a caller's objective
+def test_grid_search_on_the_makespan_objective_is_the_plain_grid_search():
+    rng = random.Random(21)
+    for _ in range(12):
+        p = rng.randint(2, 5)
+        g = rng.choice([1, 2, 4])
+        C = g * rng.randint(8 * p, 30 * p)
+        cost = lambda prefix, c: c * (2 * prefix + c) + 40.0 * c
+        want_b, want_m, _ = kvra.kvra_search_grid(C, p, g, cost)
+        got_b, got_m, evals = kvra.kvra_search_grid_objective(C, p, g, lambda b: orc.makespan(b, cost))
+        assert (got_b, got_m) == (want_b, want_m)
+        ob, om, _ = orc.hierarchical_grid_search(C, p, g, objective=lambda b: orc.makespan(b, cost))
+        assert (got_b, got_m) == (ob, om)
+        assert evals <= 1 + len(orc.grid_search_strides(C, p, g)) * 5 ** (p - 1)
+
+
+def test_grid_search_on_the_chain_ttft_matches_the_oracle_and_never_loses_to_its_start():
+    rng = random.Random(22)
+    for _ in range(10):
+        p = rng.randint(2, 4)
+        g = rng.choice([2, 4, 8])
+        C = g * rng.randint(8 * p, 24 * p)
+        L = rng.randint(1, 12)
+        before = lambda prefix, c: 0.5 + 0.05 * c
+        attend = lambda prefix, c: 1e-3 * c * (2 * prefix + c)
+        send = lambda prefix, c: 0.01 * (prefix + c)
+        ttft = lambda b: orc.chain_ttft(b, L, before, attend, send)
+        start = orc.sqrt_rule(C, p, g) if rng.random() < 0.5 else None
+        if start is not None and any(start[i + 1] <= start[i] for i in range(p)):
+            start = None
+        got_b, got_v, _ = kvra.kvra_search_grid_objective(C, p, g, ttft, start=start)
+        want_b, want_v, _ = orc.hierarchical_grid_search(C, p, g, start=start, objective=ttft)
+        assert got_b == want_b and got_v == want_v
+        assert got_v == ttft(got_b)
+        assert got_v <= ttft(start if start is not None else orc.equal_split(C, p, g))
+
+
+def test_grid_search_objective_rejects_bad_arguments():
+    with pytest.raises(kvra.KvraError):
+        kvra.kvra_search_grid_objective(1100, 11, 1, lambda b: 0.0)           # 5^10 combinations per level
+    with pytest.raises(kvra.KvraError):
+        kvra.kvra_search_grid_objective(96, 3, 5, lambda b: 0.0)              # not on the grid
+    with pytest.raises(kvra.KvraError):
+        kvra.kvra_search_grid_objective(96, 3, 4, lambda b: float("nan"))
+    with pytest.raises(kvra.KvraError):
+        kvra.kvra_search_grid_objective(96, 3, 4, lambda b: 0.0, start=[0, 30, 64, 96])   # start off the grid
