@@ -347,6 +347,8 @@ def main():
                      "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": ATTN_TRAFFIC_BYTES if args.workload == WORKLOAD else None,
                      "avg_launch_ms": attn_avg_launch_ms},
         "per_chunk": {"attn_ms": [round(float(x), 4) for x in attn_mean],
+                      "attn_ms_median": [round(float(x), 4) for x in np.median(attn_ms, axis=0)],
+                      "attn_ms_min": [round(float(x), 4) for x in attn_ms.min(axis=0)],
                       "append_ms": [round(float(x), 4) for x in append_mean],
                       "attn_tflops": [round(flops_chunk[i] / (attn_mean[i] * 1e-3) / 1e12, 1) for i in range(p)]},
         "append_kv": {"bound": "hbm", "achieved": append_gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
