@@ -395,3 +395,36 @@ def test_grid_search_objective_rejects_bad_arguments():
         kvra.kvra_search_grid_objective(96, 3, 4, lambda b: float("nan"))
     with pytest.raises(kvra.KvraError):
         kvra.kvra_search_grid_objective(96, 3, 4, lambda b: 0.0, start=[0, 30, 64, 96])   # start off the grid
+
+
+def test_header_is_plain_c_and_a_c_program_can_call_the_host_entry_points(tmp_path):
+    """The boundary is a C ABI: the header compiles as C99, and a C program linked against the
+    library gets the same partition as the Python binding."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    header_dir = os.path.join(ROOT, "include")
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c",
+                    os.path.join(header_dir, "kvra.h")], check=True)
+    src = tmp_path / "host.c"
+    src.write_text(
+        '#include <stdio.h>\n#include "kvra.h"\n'
+        "int main(void) {\n"
+        "  int64_t b[9]; double m = 0; kvra_attn_plan plan;\n"
+        "  if (kvra_balance(16384, 8, 64, NULL, NULL, b, &m) != KVRA_OK) return 1;\n"
+        "  if (kvra_chunk_attn_plan(b[7], b[8] - b[7], 32, 32, 128, 256, &plan) != KVRA_OK) return 2;\n"
+        '  for (int k = 0; k < 9; ++k) printf("%lld ", (long long)b[k]);\n'
+        '  printf("| %d %d %d %s\\n", plan.whole_units, plan.split_units, plan.segments, kvra_strerror(KVRA_ERANGE));\n'
+        "  return 0;\n}\n")
+    exe = tmp_path / "host"
+    lib_dir = os.path.dirname(kvra.LIB_PATH)
+    subprocess.run([gcc, "-std=c99", "-I", header_dir, str(src), "-o", str(exe), "-L", lib_dir, "-l:libkvra.so",
+                    "-Wl,-rpath," + lib_dir, "-Wl,--allow-shlib-undefined"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout
+    bounds, rest = out.split("|")
+    want_b = kvra.kvra_balance(16384, 8, 64)[0]
+    assert [int(x) for x in bounds.split()] == want_b
+    plan = kvra.kvra_chunk_attn_plan(want_b[7], want_b[8] - want_b[7], 32, 32, 128, 256)
+    assert [int(x) for x in rest.split()[:3]] == [plan["whole_units"], plan["split_units"], plan["segments"]]
