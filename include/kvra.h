@@ -16,13 +16,17 @@
  *   - head_dim must be 64 or 128; n_q_heads must be a multiple of n_kv_heads; query head h
  *     reads key/value head h / (n_q_heads / n_kv_heads).
  *   - The only state the library keeps is one scratch buffer per device (about 100 MB, hipMalloc'ed
- *     by the first kvra_chunk_attn call on that device, kept until the process ends).  It holds
- *     the partial results of key-split launches, which kvra_chunk_attn takes when the (kv head,
- *     256-row tile) units of a call do not fill the last round of the device's CUs - e.g. a short
- *     chunk behind a long prefix.
- *     Two such calls (kvra_layer_chunk included) that overlap in time on one device, from
- *     different streams, would share it and are not supported.  If the allocation fails the call
- *     runs without key-splitting.
+ *     by the first kvra_chunk_attn call on that device that is allowed to allocate, kept until the
+ *     process ends).  It holds the partial results of key-split launches, which kvra_chunk_attn
+ *     takes when the (kv head, 256-row tile) units of a call do not fill the last round of the
+ *     device's CUs - e.g. a short chunk behind a long prefix.  While there is no buffer - the
+ *     allocation failed, or `stream` is being captured into a graph, where allocating is illegal -
+ *     a call runs without key-splitting (same results up to rounding order, slower on such shapes)
+ *     and the next call tries again; to have key-split launches inside a captured graph, make one
+ *     kvra_chunk_attn call on the device before the capture starts.  The buffer belongs to the
+ *     device that is current when the call is made, which must be the device of `stream`.
+ *     Two key-split calls (kvra_layer_chunk included) that overlap in time on one device, from
+ *     different streams, share the buffer and race: not supported, not detected.
  */
 #ifndef KVRA_H
 #define KVRA_H

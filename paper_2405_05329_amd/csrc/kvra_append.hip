@@ -26,8 +26,10 @@ __device__ __forceinline__ float bf16_to_f32(unsigned short b) {
 }
 
 __device__ __forceinline__ unsigned short f32_to_bf16_rne(float x) {
-  // round to nearest, ties to even, on the bit pattern (inputs are finite)
+  // round to nearest, ties to even, on the bit pattern; a NaN stays a (quiet) NaN instead of
+  // being carried into an infinity or a zero by the rounding increment
   unsigned int u = __float_as_uint(x);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return static_cast<unsigned short>((u >> 16) | 0x0040u);
   u += 0x7FFFu + ((u >> 16) & 1u);
   return static_cast<unsigned short>(u >> 16);
 }

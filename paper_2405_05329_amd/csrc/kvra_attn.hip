@@ -602,22 +602,38 @@ float* g_scratch[kMaxDevices] = {};
 int g_cus[kMaxDevices] = {};
 std::mutex g_scratch_mutex;
 
-float* device_scratch(int* cus_out) {
+// Compute units of the current device (0 if it cannot be asked); cached per device.
+int device_cus(int dev) {
+  if (g_cus[dev] == 0) {
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus >= 8) g_cus[dev] = cus;
+  }
+  return g_cus[dev];
+}
+
+// The allocated scratch of the current device, or nullptr (the caller then launches without key-split).
+// A failed attempt is not remembered: a call made while `stream` is being captured (an allocation
+// would be illegal there) or while memory is short runs unsplit, and a later call tries again.
+float* device_scratch(hipStream_t stream, int* cus_out) {
+  *cus_out = 0;
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
   std::lock_guard<std::mutex> lock(g_scratch_mutex);
-  if (g_cus[dev] == 0) {
-    int cus = 0;
-    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 8) cus = -1;
-    g_cus[dev] = cus;
-    if (cus > 0) {
-      const size_t bytes = static_cast<size_t>(kSlotsPerCu) * cus * kPartialFloats(128) * sizeof(float);
-      void* p = nullptr;
-      if (hipMalloc(&p, bytes) == hipSuccess) g_scratch[dev] = static_cast<float*>(p);
-      else (void)hipGetLastError();   // leave no sticky error behind; the plain launch needs no scratch
+  const int cus = device_cus(dev);
+  *cus_out = cus;
+  if (cus <= 0) return nullptr;
+  if (g_scratch[dev] == nullptr) {
+    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &capturing) != hipSuccess) {
+      (void)hipGetLastError();
+      return nullptr;
     }
+    if (capturing != hipStreamCaptureStatusNone) return nullptr;
+    const size_t bytes = static_cast<size_t>(kSlotsPerCu) * cus * kPartialFloats(128) * sizeof(float);
+    void* p = nullptr;
+    if (hipMalloc(&p, bytes) == hipSuccess) g_scratch[dev] = static_cast<float*>(p);
+    else (void)hipGetLastError();   // leave no sticky error behind; the plain launch needs no scratch
   }
-  *cus_out = g_cus[dev];
   return g_scratch[dev];
 }
 
@@ -684,7 +700,7 @@ int launch_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
                       int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_kv_heads, int head_dim,
                       float scale, void* out, hipStream_t stream) {
   int cus = 0;
-  float* scratch = device_scratch(&cus);
+  float* scratch = device_scratch(stream, &cus);
   AttnPlan plan;
   const int rc0 = plan_chunk_attn(prefix_len, chunk_len, n_q_heads, n_kv_heads, head_dim, cus, scratch != nullptr, &plan);
   if (rc0 != KVRA_OK) return rc0;

@@ -95,6 +95,34 @@ def test_append_without_rope_is_a_bit_exact_copy():
     np.testing.assert_array_equal(to_bits(dq), q)
 
 
+def test_append_keeps_nan_and_inf_recognisable():
+    """Bad input stays visible: a NaN in K or Q comes out as a NaN (not as an infinity or a zero made
+    by the rounding step), an infinity as an infinity or NaN, and V is still a bit copy."""
+    import torch
+    from gpu_pipeline import to_dev, to_bits
+    from paper_2405_05329_amd import kvra
+    H, Hkv, d, c = 2, 2, 64, 5
+    q, k, v = synth.make_qkv(6, 92, c, H, Hkv, d)
+    k[1, 0, 3] = 0x7FFF     # NaN with every mantissa bit set: +0x7FFF rounding would carry it into the sign
+    k[2, 1, 40] = 0xFFFF
+    q[3, 1, 7] = 0x7FC0
+    k[4, 0, 5] = 0x7F80     # +inf
+    v[0, 0, 0] = 0x7FFF
+    kc = to_dev(np.zeros((c, Hkv, d), dtype=np.uint16))
+    vc = to_dev(np.zeros((c, Hkv, d), dtype=np.uint16))
+    dq = to_dev(q)
+    kvra.kvra_append_kv(to_dev(k), to_dev(v), dq, kc, vc, 0, c, c, H, Hkv, d, synth.ROPE_BASE)
+    torch.cuda.synchronize()
+    kf, qf = _f64(to_bits(kc)), _f64(to_bits(dq))
+    np.testing.assert_array_equal(to_bits(vc), v)
+    # a NaN reaches both members of its rotation pair (i, i + d/2) and nothing else
+    assert np.isnan(kf[1, 0, 3]) and np.isnan(kf[1, 0, 3 + d // 2])
+    assert np.isnan(kf[2, 1, 40]) and np.isnan(kf[2, 1, 40 - d // 2])
+    assert np.isnan(qf[3, 1, 7]) and np.isnan(qf[3, 1, 7 + d // 2])
+    assert not np.isfinite(kf[4, 0, 5]) and not np.isfinite(kf[4, 0, 5 + d // 2])
+    assert np.isnan(kf).sum() + np.isinf(kf).sum() == 6 and np.isnan(qf).sum() == 2
+
+
 # ------------------------------------------------------------------------------- attention, small
 @pytest.mark.parametrize("seed", [0, 1, 2])
 def test_tiny_config_full(seed):
