@@ -43,7 +43,8 @@ enum {
   KVRA_EUNSUPPORTED = -2, /* head_dim other than 64 / 128, or a size beyond the 32-bit tiling   */
   KVRA_ERANGE = -3,       /* prefix_len + chunk_len exceeds the cache capacity                  */
   KVRA_ELAUNCH = -4,      /* the HIP runtime refused the launch                                  */
-  KVRA_ENODEVICE = -5     /* no usable gfx950 device                                            */
+  KVRA_ENODEVICE = -5,    /* no usable gfx950 device                                            */
+  KVRA_ESCRATCH = -6      /* kvra_chunk_attn_noalloc: the launch needs more scratch than it owns */
 };
 
 /* Human-readable text for a return code (static storage, never NULL). */
@@ -94,6 +95,30 @@ int kvra_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
                     int64_t prefix_len, int64_t chunk_len,
                     int n_q_heads, int n_kv_heads, int head_dim,
                     float scale, void* out, void* stream);
+
+/*
+ * kvra_chunk_attn for callers that cannot allocate device memory: code that runs under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same
+ * launch plan and therefore the same results bit for bit; it calls no hipMalloc / hipFree and no
+ * allocating library routine.  The partial results of key-split launches go to a fixed array in the
+ * library's device image instead of the allocated buffer: kvra_chunk_attn_noalloc_scratch_bytes()
+ * bytes (99 MiB = 768 partial-result slots, three per compute unit of a 256-CU device), which every
+ * GPU the library is loaded on holds until the process ends.  Its device address is looked up on the
+ * first call on each device (hipGetSymbolAddress, no allocation).
+ *   - A call whose launch plan (kvra_chunk_attn_plan with the device's CU count) needs more than
+ *     that - possible only on a device with more than 256 CUs - returns KVRA_ESCRATCH and enqueues
+ *     nothing.  KVRA_ENODEVICE: the array's address could not be obtained.
+ *   - Nothing in the array has to start at zero (every slot is written in full by the kernel before
+ *     the merge kernel reads it), so calls need no clearing in between; the contents after a call
+ *     are scratch.
+ *   - All calls on one GPU share the array: two calls that overlap in time on one device (different
+ *     streams, or two graphs replayed concurrently) race.  Calls on one stream are ordered and safe.
+ */
+int kvra_chunk_attn_noalloc(const void* q, const void* k_cache, const void* v_cache,
+                            int64_t prefix_len, int64_t chunk_len,
+                            int n_q_heads, int n_kv_heads, int head_dim,
+                            float scale, void* out, void* stream);
+int64_t kvra_chunk_attn_noalloc_scratch_bytes(void);
 
 /*
  * How kvra_chunk_attn cuts the chunk's trapezoid of (query, key) pairs (Fig. 2(c), Sec. 4.1) into

@@ -25,6 +25,7 @@ extern "C" const char* kvra_strerror(int code) {
     case KVRA_ERANGE: return "prefix_len + chunk_len exceeds cache capacity";
     case KVRA_ELAUNCH: return "HIP launch or allocation failed";
     case KVRA_ENODEVICE: return "no usable gfx950 device";
+    case KVRA_ESCRATCH: return "launch needs more scratch than the fixed buffer of kvra_chunk_attn_noalloc holds";
     default: return "unknown error";
   }
 }
@@ -48,10 +49,11 @@ extern "C" int kvra_append_kv(const void* k_in, const void* v_in, void* q_inout,
                                 static_cast<hipStream_t>(stream));
 }
 
-extern "C" int kvra_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
-                               int64_t prefix_len, int64_t chunk_len,
-                               int n_q_heads, int n_kv_heads, int head_dim,
-                               float scale, void* out, void* stream) {
+namespace {
+
+int chunk_attn_checked(const void* q, const void* k_cache, const void* v_cache,
+                       int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_kv_heads, int head_dim,
+                       float scale, void* out, void* stream, bool static_scratch_only) {
   if (q == nullptr || k_cache == nullptr || v_cache == nullptr || out == nullptr) return KVRA_EINVAL;
   if (chunk_len < 1 || prefix_len < 0) return KVRA_EINVAL;
   if (!(scale > 0.0f) || !(scale < INFINITY)) return KVRA_EINVAL;
@@ -59,8 +61,28 @@ extern "C" int kvra_chunk_attn(const void* q, const void* k_cache, const void* v
   if (rc != KVRA_OK) return rc;
   if (chunk_len > kMaxTokens || prefix_len > kMaxTokens) return KVRA_EUNSUPPORTED;
   return kvra::launch_chunk_attn(q, k_cache, v_cache, prefix_len, chunk_len, n_q_heads, n_kv_heads,
-                                 head_dim, scale, out, static_cast<hipStream_t>(stream));
+                                 head_dim, scale, out, static_cast<hipStream_t>(stream), static_scratch_only);
 }
+
+}  // namespace
+
+extern "C" int kvra_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
+                               int64_t prefix_len, int64_t chunk_len,
+                               int n_q_heads, int n_kv_heads, int head_dim,
+                               float scale, void* out, void* stream) {
+  return chunk_attn_checked(q, k_cache, v_cache, prefix_len, chunk_len, n_q_heads, n_kv_heads, head_dim,
+                            scale, out, stream, false);
+}
+
+extern "C" int kvra_chunk_attn_noalloc(const void* q, const void* k_cache, const void* v_cache,
+                                       int64_t prefix_len, int64_t chunk_len,
+                                       int n_q_heads, int n_kv_heads, int head_dim,
+                                       float scale, void* out, void* stream) {
+  return chunk_attn_checked(q, k_cache, v_cache, prefix_len, chunk_len, n_q_heads, n_kv_heads, head_dim,
+                            scale, out, stream, true);
+}
+
+extern "C" int64_t kvra_chunk_attn_noalloc_scratch_bytes(void) { return kvra::attn_static_scratch_bytes(); }
 
 extern "C" int kvra_chunk_attn_plan(int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_kv_heads,
                                     int head_dim, int n_cus, kvra_attn_plan* plan) {

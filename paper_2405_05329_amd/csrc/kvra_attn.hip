@@ -639,6 +639,39 @@ float* device_scratch(hipStream_t stream, int* cus_out) {
 
 }  // namespace
 
+// ---- scratch of kvra_chunk_attn_noalloc: a fixed array in the library's device image ------------
+// kStaticSlots partial-result slots = 3 per CU of a 256-CU device (what the allocating path takes
+// there, so that both entry points cut a launch the same way).  Every device the library runs on
+// holds its own copy at its own address for the life of the process.  In host code the array's
+// name is only a handle for hipGetSymbolAddress: the device address is asked for once per device,
+// with that device current, and that pointer is what the kernels get.
+constexpr int kStaticSlots = 768;
+static __device__ __align__(256) float scratch[static_cast<size_t>(kStaticSlots) * kPartialFloats(128)];
+
+namespace {
+
+float* g_static_scratch[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (nullptr on failure); no allocation.
+float* static_scratch(int* cus_out) {
+  *cus_out = 0;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  *cus_out = device_cus(dev);
+  if (g_static_scratch[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    g_static_scratch[dev] = static_cast<float*>(p);
+  }
+  return g_static_scratch[dev];
+}
+
+}  // namespace
+
 // Shape of a kvra_chunk_attn launch on a device with `cus` compute units, scratch permitting
 // (host arithmetic only).  Normally one workgroup per unit, every unit whole.  Key-split launch: the
 // units beyond the last full round of CUs (all of them when there are fewer units than CUs) are cut
@@ -696,14 +729,20 @@ int plan_chunk_attn(int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_
   return KVRA_OK;
 }
 
+int64_t attn_static_scratch_bytes() { return static_cast<int64_t>(sizeof(scratch)); }
+
 int launch_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
                       int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_kv_heads, int head_dim,
-                      float scale, void* out, hipStream_t stream) {
+                      float scale, void* out, hipStream_t stream, bool static_scratch_only) {
   int cus = 0;
-  float* scratch = device_scratch(stream, &cus);
+  float* scratch_ptr = static_scratch_only ? static_scratch(&cus) : device_scratch(stream, &cus);
+  if (static_scratch_only && scratch_ptr == nullptr) return KVRA_ENODEVICE;
   AttnPlan plan;
-  const int rc0 = plan_chunk_attn(prefix_len, chunk_len, n_q_heads, n_kv_heads, head_dim, cus, scratch != nullptr, &plan);
+  const int rc0 = plan_chunk_attn(prefix_len, chunk_len, n_q_heads, n_kv_heads, head_dim, cus, scratch_ptr != nullptr, &plan);
   if (rc0 != KVRA_OK) return rc0;
+  if (static_scratch_only &&
+      attn_partial_bytes(head_dim) * plan.split_units * plan.segments > attn_static_scratch_bytes())
+    return KVRA_ESCRATCH;
   AttnArgs a;
   a.q = static_cast<const __bf16*>(q);
   a.k = static_cast<const __bf16*>(k_cache);
@@ -718,7 +757,7 @@ int launch_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
   a.rows_per_wg = plan.rows_per_tile;
   a.c_log2 = scale * 1.4426950408889634f;
   a.bn = plan.key_tile;
-  a.scratch = plan.segments > 1 ? scratch : nullptr;
+  a.scratch = plan.segments > 1 ? scratch_ptr : nullptr;
   a.n_whole = plan.whole_units;
   a.n_split = plan.split_units;
   a.segments = plan.segments;

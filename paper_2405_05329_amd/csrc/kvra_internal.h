@@ -17,7 +17,8 @@ int launch_append_kv(const void* k_in, const void* v_in, void* q_inout, void* k_
 
 int launch_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
                       int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_kv_heads, int head_dim,
-                      float scale, void* out, hipStream_t stream);
+                      float scale, void* out, hipStream_t stream, bool static_scratch_only);
+int64_t attn_static_scratch_bytes();   // size of the fixed scratch array kvra_chunk_attn_noalloc uses
 
 // Launch shape of kvra_chunk_attn for a device with `cus` compute units (pure host arithmetic).
 struct AttnPlan {

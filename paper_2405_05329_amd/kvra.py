@@ -19,6 +19,7 @@ KVRA_EUNSUPPORTED = -2
 KVRA_ERANGE = -3
 KVRA_ELAUNCH = -4
 KVRA_ENODEVICE = -5
+KVRA_ESCRATCH = -6
 
 COST_FN = ctypes.CFUNCTYPE(ctypes.c_double, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p)
 
@@ -55,6 +56,10 @@ def _load() -> ctypes.CDLL:
     lib.kvra_append_kv.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, f32, vp]
     lib.kvra_chunk_attn.restype = i32
     lib.kvra_chunk_attn.argtypes = [vp, vp, vp, i64, i64, i32, i32, i32, f32, vp, vp]
+    lib.kvra_chunk_attn_noalloc.restype = i32
+    lib.kvra_chunk_attn_noalloc.argtypes = [vp, vp, vp, i64, i64, i32, i32, i32, f32, vp, vp]
+    lib.kvra_chunk_attn_noalloc_scratch_bytes.restype = i64
+    lib.kvra_chunk_attn_noalloc_scratch_bytes.argtypes = []
     lib.kvra_chunk_attn_plan.restype = i32
     lib.kvra_chunk_attn_plan.argtypes = [i64, i64, i32, i32, i32, i32, ctypes.POINTER(KvraAttnPlan)]
     lib.kvra_balance.restype = i32
@@ -158,6 +163,20 @@ def kvra_chunk_attn(q, k_cache, v_cache, prefix_len, chunk_len, n_q_heads, n_kv_
     if check and rc != KVRA_OK:
         raise KvraError(rc, "kvra_chunk_attn")
     return rc
+
+
+def kvra_chunk_attn_noalloc(q, k_cache, v_cache, prefix_len, chunk_len, n_q_heads, n_kv_heads, head_dim,
+                            scale, out, stream=None, check=True) -> int:
+    rc = _lib.kvra_chunk_attn_noalloc(_ptr(q), _ptr(k_cache), _ptr(v_cache), int(prefix_len), int(chunk_len),
+                                      int(n_q_heads), int(n_kv_heads), int(head_dim), float(scale),
+                                      _ptr(out), _stream(stream))
+    if check and rc != KVRA_OK:
+        raise KvraError(rc, "kvra_chunk_attn_noalloc")
+    return rc
+
+
+def kvra_chunk_attn_noalloc_scratch_bytes() -> int:
+    return int(_lib.kvra_chunk_attn_noalloc_scratch_bytes())
 
 
 def kvra_chunk_attn_plan(prefix_len, chunk_len, n_q_heads, n_kv_heads, head_dim, n_cus) -> dict:

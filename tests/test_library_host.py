@@ -6,6 +6,7 @@ import os
 import random
 import re
 
+import numpy as np
 import pytest
 
 from oracle import kvra_oracle as orc
@@ -336,6 +337,26 @@ def test_attention_launch_plan_invariants_and_decode_like_shapes():
         if p["segments"] > 1:                                               # at least 16 key tiles per piece
             last_rows = min(p["rows_per_tile"], rows)
             assert ((prefix + (last_rows - 1) // (H // Hkv)) // p["key_tile"] + 1) // p["segments"] >= 16
+
+
+def test_noalloc_scratch_holds_every_plan_of_a_256_cu_device_and_not_every_plan_of_a_larger_one():
+    """kvra_chunk_attn_noalloc refuses (KVRA_ESCRATCH) a launch whose plan needs more partial-result
+    bytes than its fixed array holds.  That array is sized for three slots per CU of a 256-CU device:
+    no plan for 256 CUs exceeds it, while a hypothetical 512-CU device has plans that do."""
+    cap = kvra.kvra_chunk_attn_noalloc_scratch_bytes()
+    assert cap == 768 * 8 * (4 * 16 + 2) * 64 * 4
+    rng = np.random.default_rng(3)
+    worst = {256: 0, 512: 0}
+    for _ in range(400):
+        d = int(rng.choice([64, 128]))
+        hkv = int(rng.choice([1, 2, 8, 32]))
+        g = int(rng.choice([1, 4, 8]))
+        prefix = int(rng.integers(0, 40000))
+        c = int(rng.integers(1, 6000))
+        for cus in worst:
+            plan = kvra.kvra_chunk_attn_plan(prefix, c, hkv * g, hkv, d, cus)
+            worst[cus] = max(worst[cus], plan["scratch_bytes"])
+    assert 0 < worst[256] <= cap < worst[512]
 
 
 def test_attention_launch_plan_rejects_bad_arguments():
