@@ -1,8 +1,10 @@
 """Parity of the HIP path (through the C-ABI) with the fp64 oracle on the same seeded bf16 inputs.
 
-Bars: attention outputs max-abs <= 2e-2 and mean-abs <= 2e-3 against the oracle evaluated in fp64
-on the un-rounded rotation; V rows and all cache indexing bit-exact; rotated K / Q within one bf16
-unit in the last place of the correctly rounded oracle value.
+Bars: attention outputs max-abs <= 2e-2 and mean-abs <= 2e-3 against the exact oracle (fp64, nothing
+rounded on the way) for the unit-scale workloads; for inputs with larger scores, the bars the rounding
+model derives for that input (tests/rounding_model.py), again against the exact oracle; V rows and all
+cache indexing bit-exact; rotated K / Q within one bf16 unit in the last place of the correctly
+rounded oracle value.
 """
 import numpy as np
 import pytest
@@ -164,25 +166,69 @@ def test_no_rope_and_other_scale():
 
 
 def test_peaky_softmax_exercises_the_rescale_path():
-    # Queries four times larger: scores have std 4, row maxima keep moving as tiles stream in and
-    # the softmax is dominated by a few keys.  The bf16 roundings of the operands of the score
-    # product (2^-9 relative each: the rotated Q and K, and the kernel's Q fragment, which carries
-    # scale * log2(e) and is rounded once more) are amplified four-fold in the exponent here, so
-    # the kernel is held to the standard bars against the oracle evaluated on operands the oracle
-    # rounded the same way itself, and to four times wider bars against the un-rounded oracle.
+    """Queries four times larger: scores have standard deviation 4, row maxima keep moving as tiles stream
+    in and a few keys carry each row.  The unit-scale bars do not apply to such inputs (the bf16 roundings
+    of the score operands are amplified by the score scale before the exponential), so the exact oracle
+    is held to the bars that the rounding model derives for this very input: every element within six
+    predicted standard deviations plus half a bf16 ulp of the result, mean-abs within 1.25 times the
+    model's expectation (tests/rounding_model.py, pinned on the CPU by tests/test_rounding_model.py)."""
+    import rounding_model as rm
     C, H, Hkv, d = 700, 4, 4, 128
     q, k, v, scale, res = _run(52, 2, C, H, Hkv, d, [0, 300, 700], q_gain=4.0)
-    pos = np.arange(C)
-    qr = _f64(orc.f64_to_bf16_bits(orc.rope(_f64(q), pos, synth.ROPE_BASE)))
-    kr = _f64(orc.f64_to_bf16_bits(orc.rope(_f64(k), pos, synth.ROPE_BASE)))
-    c_log2 = np.float32(scale) * np.float32(1.4426950408889634)       # fp32, as the launcher forms it
-    q2 = _f64(orc.f64_to_bf16_bits((qr.astype(np.float32) * c_log2).astype(np.float64)))
-    # softmax in base 2 of q2 . kr  ==  softmax in base e of ln(2) q2 . kr
-    want_rounded = orc.causal_attention(q2, kr, _f64(v), float(np.log(2.0)), rope_base=None)
-    _check_out(res["out"], want_rounded, "peaky/rounded-rotation")
-    want = orc.causal_attention(_f64(q), _f64(k), _f64(v), scale, rope_base=synth.ROPE_BASE)
+    sig, want = rm.sigma(_f64(q), _f64(k), _f64(v), scale, synth.ROPE_BASE)
+    ratio, mean_abs, mean_bar = rm.check(_f64(res["out"]), want, sig, "peaky")
     err = np.abs(_f64(res["out"]) - want)
-    assert err.max() <= 4 * MAX_ABS and err.mean() <= 4 * MEAN_ABS
+    print(f"peaky (gain 4): max-abs {err.max():.3e}, mean-abs {mean_abs:.3e} (bar {mean_bar:.3e}), "
+          f"worst element at {ratio:.2f} of its bar")
+
+
+def _stress_cases(n, seed):
+    import random
+    rng = random.Random(seed)
+    cases = []
+    for _ in range(n):
+        H, Hkv, d = rng.choice([(4, 4, 128), (8, 2, 128), (6, 1, 128), (2, 2, 64), (9, 3, 64), (71, 1, 64), (32, 32, 128)])
+        C = rng.choice([1, 2, 33, 64, 65, 130, 257, 300, 511, 700, 1100])
+        if H >= 32:
+            C = min(C, 300)
+        p = rng.randint(1, min(5, C))
+        cuts = sorted(rng.sample(range(1, C), p - 1)) if C > 1 and p > 1 else []
+        cases.append(dict(H=H, Hkv=Hkv, d=d, bounds=[0] + cuts + [C], gain=rng.choice([1.0, 1.0, 4.0, 8.0]),
+                          rope=rng.choice([synth.ROPE_BASE, synth.ROPE_BASE, None]),
+                          scale_mult=rng.choice([1.0, 0.5, 2.0]), seed=rng.randint(0, 10 ** 6),
+                          extra_capacity=rng.randint(0, 3)))
+    return cases
+
+
+def test_seeded_stress_of_shapes_gains_and_scales():
+    """A fixed list of 80 random cases: head layouts, context lengths around the tile sizes, partitions,
+    query gains 1 / 4 / 8 times softmax scales 0.5 / 1 / 2 of the convention (score standard deviations
+    from 0.5 to 16), rotary embedding on and off.  Every output element against the exact oracle under
+    the rounding model's bars with the cheap upper bound for the Q term; 24 sampled rows x up to 4 heads
+    under the bars of the full model.  Stops at the first failure."""
+    import rounding_model as rm
+    from gpu_pipeline import run_chunked
+    rng = np.random.default_rng(99)
+    worst_full, worst_bound = 0.0, 0.0
+    for n, cs in enumerate(_stress_cases(80, 20240601)):
+        H, Hkv, d, b = cs["H"], cs["Hkv"], cs["d"], cs["bounds"]
+        C = b[-1]
+        q, k, v = synth.make_qkv(cs["seed"], 300 + n, C, H, Hkv, d, q_gain=cs["gain"])
+        scale = synth.default_scale(d) * cs["scale_mult"]
+        res = run_chunked(q, k, v, b, scale, cs["rope"], capacity=C + cs["extra_capacity"])
+        got = _f64(res["out"])
+        label = f"case {n}: {H}/{Hkv} d{d} {b} gain {cs['gain']} scale x{cs['scale_mult']} rope {cs['rope']}"
+        sig_b, want = rm.sigma(_f64(q), _f64(k), _f64(v), scale, cs["rope"], exact_q_term=False)
+        r_bound, _, _ = rm.check(got, want, sig_b, label + " (all elements)")
+        rows = sorted({0, C - 1} | {x for x in b[1:-1]} | {int(x) for x in rng.integers(0, C, size=20)})[:24]
+        heads = sorted({int(x) for x in rng.choice(H, size=min(H, 4), replace=False)})
+        sig, want_s = rm.sigma(_f64(q), _f64(k), _f64(v), scale, cs["rope"], rows=rows, heads=heads)
+        r_full, _, _ = rm.check(got[rows][:, heads], want_s, sig, label + " (sampled rows, full model)")
+        worst_full, worst_bound = max(worst_full, r_full), max(worst_bound, r_bound)
+        np.testing.assert_array_equal(res["v_cache"][:C], v)
+        if n % 10 == 9:
+            print(f"stress: {n + 1} cases, worst element at {worst_full:.2f} (full model) / {worst_bound:.2f} (bound) of its bar",
+                  flush=True)
 
 
 def test_first_row_returns_first_value_row():
@@ -192,17 +238,19 @@ def test_first_row_returns_first_value_row():
 
 
 def test_partition_invariance_on_gpu():
-    # any partition gives the same result up to rounding order; compare both with the oracle
+    # any partition gives the same result up to rounding order: both against the oracle, the rotated
+    # operands bit for bit against each other
     C, H, Hkv, d = 512, 4, 4, 128
     q, k, v = synth.make_qkv(5, 54, C, H, Hkv, d)
     from gpu_pipeline import run_chunked
     scale = synth.default_scale(d)
     a = run_chunked(q, k, v, [0, 512], scale, synth.ROPE_BASE)
     b = run_chunked(q, k, v, [0, 100, 228, 229, 512], scale, synth.ROPE_BASE)
+    want = orc.causal_attention(_f64(q), _f64(k), _f64(v), scale, rope_base=synth.ROPE_BASE)
+    _check_out(a["out"], want, "one chunk")
+    _check_out(b["out"], want, "four chunks")
     np.testing.assert_array_equal(a["k_cache"], b["k_cache"])
     np.testing.assert_array_equal(a["q_rot"], b["q_rot"])
-    diff = np.abs(_f64(a["out"]) - _f64(b["out"]))
-    assert diff.max() <= 2e-2
 
 
 # ------------------------------------------------------------------------------- attention, paper shapes
@@ -212,6 +260,27 @@ def test_llama7b_4k_equal_chunks_full():
     want = orc.causal_attention(_f64(q), _f64(k), _f64(v), scale, rope_base=synth.ROPE_BASE)
     mx, mean = _check_out(res["out"], want, "llama 4k")
     print(f"llama7b 4k: max-abs {mx:.3e} mean-abs {mean:.3e}")
+    np.testing.assert_array_equal(res["v_cache"], v)
+
+
+def test_llama7b_16k_balanced_every_element():
+    """The workload the metric is quoted on, every output element (16384 x 32 x 128) against the oracle."""
+    cfg = synth.CONFIGS["llama7b_16k_balanced"]
+    q, k, v, scale, res = _run(cfg["cfg_id"], 0, cfg["C"], cfg["H"], cfg["Hkv"], cfg["d"], cfg["boundaries"])
+    got = _f64(res["out"])
+    assert np.all(np.isfinite(got))
+    qf, kf, vf = _f64(q), _f64(k), _f64(v)
+    pos = np.arange(cfg["C"])
+    qf, kf = orc.rope(qf, pos, synth.ROPE_BASE), orc.rope(kf, pos, synth.ROPE_BASE)
+    worst, total = 0.0, 0.0
+    for h0 in range(0, cfg["H"], 4):         # four heads at a time keeps the oracle's weight matrices in memory
+        want = orc.causal_attention(qf[:, h0:h0 + 4], kf[:, h0:h0 + 4], vf[:, h0:h0 + 4], scale, rope_base=None)
+        err = np.abs(got[:, h0:h0 + 4] - want)
+        worst, total = max(worst, float(err.max())), total + float(err.sum())
+        assert err.max() <= MAX_ABS, f"heads {h0}..{h0 + 3}: max-abs {err.max():.3e}"
+    mean = total / got.size
+    assert mean <= MEAN_ABS
+    print(f"llama7b 16k balanced, all {got.size} elements: max-abs {worst:.3e} mean-abs {mean:.3e}")
     np.testing.assert_array_equal(res["v_cache"], v)
 
 
