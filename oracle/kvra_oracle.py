@@ -538,3 +538,51 @@ def decoder_layer(x, weights, n_q_heads, n_kv_heads, head_dim, scale, rope_base,
         h2 = rnd(rms_norm(x2, weights["norm2"], eps))
         y[lo:hi] = rnd(x2 + swiglu_mlp(h2, weights["w_gate"], weights["w_up"], weights["w_down"], rnd))
     return y, k_cache, v_cache
+
+
+def layer_kv_cache(x, weights, n_kv_heads, head_dim, rope_base, eps, rnd=_no_rounding):
+    """K (rotated) and V of every token of the context x [C, hidden]: what the rows of later chunks see of
+    earlier ones (App. C listing: the cache each process hands on).  Returns (k [C, H_kv, d], v)."""
+    C = x.shape[0]
+    h1 = rnd(rms_norm(x, weights["norm1"], eps))
+    k = rnd(linear(h1, weights["wk"])).reshape(C, n_kv_heads, head_dim)
+    v = rnd(linear(h1, weights["wv"])).reshape(C, n_kv_heads, head_dim)
+    if rope_base is not None:
+        k = rnd(rope(k, np.arange(C), rope_base))
+    return k, v
+
+
+def decoder_layer_rows(x, weights, n_q_heads, n_kv_heads, head_dim, scale, rope_base, eps, rows,
+                       rnd=_no_rounding, cache=None):
+    """Rows `rows` (absolute positions) of decoder_layer's output, evaluated one row at a time so that a long
+    context can be checked on a sample: a row depends on earlier rows only through their K and V.
+
+    cache: (k, v) from layer_kv_cache, or None to compute it here (with the same rnd).  Everything after
+    the cache - query projection, rotation, attention over keys 0..t, output projection, residual, norm,
+    SwiGLU MLP, residual - is done for the requested rows only, same steps as decoder_layer.
+    Returns (y [len(rows), hidden], x2 [len(rows), hidden])."""
+    H, Hkv, d = n_q_heads, n_kv_heads, head_dim
+    rows = [int(r) for r in rows]
+    tmax = max(rows) + 1
+    k, v = cache if cache is not None else layer_kv_cache(x[:tmax], weights, Hkv, d, rope_base, eps, rnd)
+    y = np.empty((len(rows), x.shape[1]))
+    x2s = np.empty_like(y)
+    for n, t in enumerate(rows):
+        xt = x[t:t + 1]
+        h1 = rnd(rms_norm(xt, weights["norm1"], eps))
+        q = rnd(linear(h1, weights["wq"])).reshape(1, H, d)
+        if rope_base is not None:
+            q = rnd(rope(q, np.array([t]), rope_base))
+        a = np.empty((1, H, d))
+        for h in range(H):
+            g = _kv_head(h, H, Hkv)
+            s = scale * (k[:t + 1, g, :] @ q[0, h, :])
+            w = np.exp(s - s.max())
+            a[0, h, :] = (w / w.sum()) @ v[:t + 1, g, :]
+        a = rnd(a)
+        x2 = rnd(xt + linear(a.reshape(1, H * d), weights["wo"]))
+        h2 = rnd(rms_norm(x2, weights["norm2"], eps))
+        y[n] = rnd(x2 + swiglu_mlp(h2, weights["w_gate"], weights["w_up"], weights["w_down"], rnd))[0]
+        x2s[n] = x2[0]
+    return y, x2s
+

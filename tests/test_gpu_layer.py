@@ -3,16 +3,19 @@ bf16 inputs.
 
 Bars.  A single operator (RMSNorm, linear layer) computes in fp32 and rounds once to bf16: it must
 lie within one bf16 unit in the last place of the oracle value, |err| <= 2^-8 |want| + 1e-4.  The
-whole layer stores six intermediate tensors in bf16 and is compared with the oracle run with the
-same storage roundings.  The two sides disagree by one unit in the last place on part of the stored
-elements (the attention kernel rounds P to bf16, fp32 versus fp64 accumulation flips roundings);
-each linear stage passes such a perturbation on with gain weight_std * sqrt(fan_in) (1.3 - 2.1 at
-the LLaMA-7B shape), a flip of x2 = x + attention branch reaches the output directly through the
-residual, and the output's own rounding adds one more unit.  Measured noise at the LLaMA-7B shape:
-mean 6.5e-3, max 6.3e-2 for |x2| + |y| of 2.9 on average.  Bars (about twice that):
-|err| <= 4e-2 + 2^-6 (|x2| + |y|), mean-abs <= 1e-3 + 2^-8 mean(|x2| + |y|); against the exact oracle
-(no storage rounding) |err| <= 8e-2 + 2^-5 (|x2| + |y|).  A structural mistake (dropped residual or
-gain, wrong head mapping, transposed weight) shows as errors of order 1.
+whole layer stores its intermediate tensors in bf16, and a flipped rounding upstream changes
+everything downstream by about a unit in the last place, amplified by every linear stage (gain
+weight_std * sqrt(fan_in): 1.3 - 2.1 at the LLaMA-7B shape): no two implementations of the same precision
+reading agree closely, and neither agrees closely with the exact layer.  The yardstick for "how far from
+the exact layer may a faithful bf16 implementation be" is therefore computed, not chosen: the oracle run
+with bf16 storage of every intermediate, minus the exact oracle, gives a per-row root mean square s_t.
+The kernel's output is compared with the EXACT oracle and must satisfy, in every row t,
+rms_t(got - exact) <= 1.25 s_t and |got - exact| <= 6 s_t + half a bf16 ulp of the result, and over all
+rows together rms(got - exact) <= 1.1 rms(stored - exact).  (The kernels add to the storage roundings only
+the rounding of P and the second rounding of the Q fragment inside the attention, a few per cent; measured:
+the row ratio is 1.03 +- 0.03, worst of 777 rows 1.12.)  The oracle with storage rounding is never the
+expected value.  A structural mistake (dropped residual or gain,
+wrong head mapping, transposed weight) shows as errors of order 1, some 100 s_t.
 """
 import numpy as np
 import pytest
@@ -142,6 +145,46 @@ def _run_layer(cfg_id, seed, C, hidden, ffn, H, Hkv, d, weight_std, boundaries):
     return _f64(x), weights, scale, _f64(to_bits(y)), _f64(to_bits(k_cache)), _f64(to_bits(v_cache))
 
 
+def _bf16_storage_fast(t):
+    """bf16 storage rounding of a large fp64 array through torch (multi-threaded).  torch narrows via fp32,
+    which can differ from the oracle's own direct rounding on a tie about once in 2^16 elements: of no
+    consequence for a yardstick, and 20 times faster on the 134 M-element tensors of the 32k context."""
+    return torch.from_numpy(np.ascontiguousarray(t)).to(torch.bfloat16).to(torch.float64).numpy()
+
+
+def _layer_bars(got, exact, stored, label):
+    """got, exact, stored: [rows, hidden].  Per-row yardstick s_t = rms_t(stored - exact); see the header."""
+    assert np.all(np.isfinite(got)), label
+    s_t = np.sqrt(np.mean((stored - exact) ** 2, axis=1, keepdims=True))
+    err = got - exact
+    rms_t = np.sqrt(np.mean(err ** 2, axis=1, keepdims=True))
+    ulp = np.exp2(np.floor(np.log2(np.maximum(np.abs(exact), 2.0 ** -100))) - 7.0)
+    worst_rms = float((rms_t / s_t).max())
+    worst_el = float((np.abs(err) / (6.0 * s_t + 0.5 * ulp)).max())
+    print(f"{label}: rows {got.shape[0]}, yardstick rms {float(np.sqrt(np.mean(s_t ** 2))):.3e}, kernel rms "
+          f"{float(np.sqrt(np.mean(err ** 2))):.3e}, worst row at {worst_rms:.2f} of 1.25, worst element at "
+          f"{worst_el:.2f} of its bar, max-abs {np.abs(err).max():.3e}")
+    assert worst_rms <= 1.25, f"{label}: a row's rms error is {worst_rms:.2f} x the storage-rounding yardstick"
+    overall = float(np.sqrt(np.mean(err ** 2) / np.mean(s_t ** 2)))
+    assert overall <= 1.1, f"{label}: rms error over all rows is {overall:.2f} x the yardstick"
+    assert worst_el <= 1.0, f"{label}: an element is at {worst_el:.2f} of its bar"
+
+
+def _cache_bars(kc, vc, k_exact, v_exact, h1_norm, weight_std, label):
+    """Cache rows the layer wrote, against the exact K (rotated) and V [rows, Hkv, d].  The projections see
+    h1 = norm(x) stored in bf16: each output is off by a sum of fan_in independent terms, standard deviation
+    s = rho * weight_std * |h1|_2 (rho = 1.66e-3, the root mean square relative rounding error of bf16); then
+    one storage rounding (2^-8 relative), and for K one more after the rotation, which mixes component i
+    with i + d/2 (so the relative term is taken on the magnitude of the pair)."""
+    rho = 2.0 ** -7 * np.sqrt(0.375 / np.log(2.0) / 12.0)
+    s = (rho * weight_std * h1_norm)[:, None, None]
+    d = k_exact.shape[-1]
+    pair = np.sqrt(k_exact[..., :d // 2] ** 2 + k_exact[..., d // 2:] ** 2)
+    pair = np.concatenate([pair, pair], axis=-1)
+    assert np.max(np.abs(vc - v_exact) - (6.0 * s + 2.0 ** -8 * np.abs(v_exact))) <= 0, label + ": V cache"
+    assert np.max(np.abs(kc - k_exact) - (6.0 * s + 2.0 ** -7 * pair)) <= 0, label + ": K cache"
+
+
 @pytest.mark.parametrize("C,hidden,ffn,H,Hkv,d,std,bounds", [
     (300, 256, 448, 4, 2, 64, 0.06, [0, 130, 300]),
     (200, 512, 1024, 4, 4, 128, 0.045, [0, 1, 65, 200]),
@@ -149,19 +192,54 @@ def _run_layer(cfg_id, seed, C, hidden, ffn, H, Hkv, d, weight_std, boundaries):
 ])
 def test_layer_chunked(C, hidden, ffn, H, Hkv, d, std, bounds):
     x, weights, scale, got, kc, vc = _run_layer(30, 0, C, hidden, ffn, H, Hkv, d, std, bounds)
+    stored, _, _ = orc.decoder_layer(x, weights, H, Hkv, d, scale, synth.ROPE_BASE, synth.RMS_EPS,
+                                     boundaries=bounds, rnd=orc.round_to_bf16)
+    exact, ks, vs = orc.decoder_layer(x, weights, H, Hkv, d, scale, synth.ROPE_BASE, synth.RMS_EPS)
+    _layer_bars(got, exact, stored, f"layer {hidden}/{ffn} C={C} {bounds}")
+    h1_norm = np.linalg.norm(orc.rms_norm(x, weights["norm1"], synth.RMS_EPS), axis=1)
+    _cache_bars(kc, vc, ks, vs, h1_norm, std, f"layer {hidden}/{ffn} C={C}")
+
+
+def test_layer_full_width_chunks_of_several_row_tiles_behind_a_prefix():
+    """LLaMA-7B width (4096 / 11008, 32 x 128); chunks of 520 and 257 tokens: more than one 256-token tile of
+    the linear kernels and of the attention kernel per chunk, the second chunk behind a 520-token prefix."""
+    shp = synth.LAYER_SHAPES["llama7b"]
+    C, bounds = 777, [0, 520, 777]
+    hidden, ffn, H, Hkv, d, std = shp["hidden"], shp["ffn"], shp["H"], shp["Hkv"], shp["d"], shp["weight_std"]
+    x, weights, scale, got, kc, vc = _run_layer(31, 1, C, hidden, ffn, H, Hkv, d, std, bounds)
+    stored, _, _ = orc.decoder_layer(x, weights, H, Hkv, d, scale, synth.ROPE_BASE, synth.RMS_EPS,
+                                     boundaries=bounds, rnd=orc.round_to_bf16)
+    exact, ks, vs = orc.decoder_layer(x, weights, H, Hkv, d, scale, synth.ROPE_BASE, synth.RMS_EPS)
+    _layer_bars(got, exact, stored, "layer 4096/11008 C=777 [0, 520, 777]")
+    h1_norm = np.linalg.norm(orc.rms_norm(x, weights["norm1"], synth.RMS_EPS), axis=1)
+    _cache_bars(kc, vc, ks, vs, h1_norm, std, "layer 4096/11008 C=777")
+
+
+def test_layer_32k_balanced_chunks_sampled_rows():
+    """The decoder-layer workload itself: 32768 tokens in the 8 balanced chunks (2112 - 11584 tokens each, prefixes
+    up to 30656), LLaMA-7B width.  The oracle computes K and V of all tokens and everything else for sampled
+    rows: first and last rows of every chunk, rows around the 256-row tile edges at chunk starts and ends,
+    random rows.  The yardstick run stores K and V of all tokens in bf16 as well (early rows see few keys, so
+    the cache's rounding reaches them undiluted)."""
+    cfg = synth.CONFIGS["llama7b_32k_balanced"]
+    shp = synth.LAYER_SHAPES["llama7b"]
+    C, bounds = cfg["C"], cfg["boundaries"]
+    hidden, ffn, H, Hkv, d, std = shp["hidden"], shp["ffn"], shp["H"], shp["Hkv"], shp["d"], shp["weight_std"]
+    x, weights, scale, got, kc, vc = _run_layer(cfg["cfg_id"], 0, C, hidden, ffn, H, Hkv, d, std, bounds)
     assert np.all(np.isfinite(got))
-    tr = {}
-    stored, ks, vs = orc.decoder_layer(x, weights, H, Hkv, d, scale, synth.ROPE_BASE, synth.RMS_EPS,
-                                       boundaries=bounds, rnd=orc.round_to_bf16, trace=tr)
-    exact, _, _ = orc.decoder_layer(x, weights, H, Hkv, d, scale, synth.ROPE_BASE, synth.RMS_EPS)
-    mag = np.abs(tr["x2"]) + np.abs(stored)
-    err = np.abs(got - stored)
-    print(f"layer {hidden}/{ffn} C={C}: vs stored-rounding oracle max {err.max():.3e} mean {err.mean():.3e}; "
-          f"vs exact max {np.abs(got - exact).max():.3e} mean {np.abs(got - exact).mean():.3e}; "
-          f"|x2|+|y| mean {mag.mean():.2f}")
-    assert np.max(err - (4e-2 + 2.0 ** -6 * mag)) <= 0
-    assert err.mean() <= 1e-3 + 2.0 ** -8 * mag.mean()
-    assert np.max(np.abs(got - exact) - (8e-2 + 2.0 ** -5 * mag)) <= 0
-    # the cache rows the layer wrote: V within one rounding of the projection, K likewise after rotation
-    assert np.max(np.abs(vc - vs) - (2.0 ** -7 * np.abs(vs) + 1e-3)) <= 0
-    assert np.max(np.abs(kc - ks) - (2.0 ** -6 * np.abs(ks) + 2e-2)) <= 0
+    rows = {0, 1, C - 1}
+    for b0, b1 in zip(bounds[:-1], bounds[1:]):
+        rows.update({b0, b0 + 1, b0 + 255, b0 + 256, b1 - 1})
+        rows.update({b0 + ((b1 - b0 - 1) // 256) * 256 - 1, b0 + ((b1 - b0 - 1) // 256) * 256})
+    rng = np.random.default_rng(17)
+    rows.update(int(r) for r in rng.integers(0, C, size=24))
+    rows = sorted(r for r in rows if 0 <= r < C)
+    cache = orc.layer_kv_cache(x, weights, Hkv, d, synth.ROPE_BASE, synth.RMS_EPS)
+    exact, _ = orc.decoder_layer_rows(x, weights, H, Hkv, d, scale, synth.ROPE_BASE, synth.RMS_EPS, rows, cache=cache)
+    cache_stored = orc.layer_kv_cache(x, weights, Hkv, d, synth.ROPE_BASE, synth.RMS_EPS, rnd=_bf16_storage_fast)
+    stored, _ = orc.decoder_layer_rows(x, weights, H, Hkv, d, scale, synth.ROPE_BASE, synth.RMS_EPS, rows,
+                                       rnd=_bf16_storage_fast, cache=cache_stored)
+    del cache_stored
+    _layer_bars(got[rows], exact, stored, f"layer 32k balanced, {len(rows)} sampled rows")
+    h1_norm = np.linalg.norm(orc.rms_norm(x[rows], weights["norm1"], synth.RMS_EPS), axis=1)
+    _cache_bars(kc[rows], vc[rows], cache[0][rows], cache[1][rows], h1_norm, std, "layer 32k balanced")

@@ -128,3 +128,46 @@ def test_storage_rounding_hook():
     assert np.max(np.abs(stored - exact)) > 0.0
     v = np.array([1.0, 1.0 + 2 ** -8, 1.0 + 3 * 2 ** -8, -(1.0 + 2 ** -8 + 2 ** -20)])
     assert orc.round_to_bf16(v).tolist() == [1.0, 1.0, 1.0 + 2 ** -6, -(1.0 + 2 ** -7)]
+
+
+def test_rows_evaluation_against_the_torch_composition_and_the_whole_layer():
+    """decoder_layer_rows / layer_kv_cache (the forms used on long contexts): the sampled rows equal the rows of
+    the layer composed from torch's operators and of decoder_layer run whole and in chunks; the cache equals
+    the one the chunked run leaves behind."""
+    rng = np.random.default_rng(21)
+    C, hidden, H, Hkv, d, ffn = 57, 48, 4, 2, 16, 80
+    wt = _weights(rng, hidden, H, Hkv, d, ffn, std=0.15)
+    x = rng.standard_normal((C, hidden))
+    rows = [0, 1, 19, 20, 56]
+    want = _torch_layer(x, wt, H, Hkv, d, 0.25, 10000.0, 1e-6)
+    tr = {}
+    whole, kc, vc = orc.decoder_layer(x, wt, H, Hkv, d, 0.25, 10000.0, 1e-6, boundaries=[0, 20, 21, 57], trace=tr)
+    y, x2 = orc.decoder_layer_rows(x, wt, H, Hkv, d, 0.25, 10000.0, 1e-6, rows)
+    np.testing.assert_allclose(y, want[rows], rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(y, whole[rows], rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(x2, tr["x2"][rows], rtol=1e-11, atol=1e-12)
+    k, v = orc.layer_kv_cache(x, wt, Hkv, d, 10000.0, 1e-6)
+    np.testing.assert_allclose(k, kc, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(v, vc, rtol=1e-12, atol=1e-13)
+    # a cache handed in is used as it is
+    y2, _ = orc.decoder_layer_rows(x, wt, H, Hkv, d, 0.25, 10000.0, 1e-6, rows, cache=(k, v))
+    np.testing.assert_allclose(y2, y, rtol=1e-13, atol=1e-14)
+    # without rotary embedding
+    y3, _ = orc.decoder_layer_rows(x, wt, H, Hkv, d, 0.25, None, 1e-6, rows)
+    np.testing.assert_allclose(y3, orc.decoder_layer(x, wt, H, Hkv, d, 0.25, None, 1e-6)[0][rows], rtol=1e-11, atol=1e-12)
+
+
+def test_rows_evaluation_with_storage_rounding_follows_the_whole_layer():
+    """With bf16 storage of every intermediate the row-at-a-time sums differ from the batched ones in the last
+    bits of fp64, which can flip a rounding now and then: all but a few elements are identical, the rest
+    differ by what one flipped rounding upstream can cause."""
+    rng = np.random.default_rng(22)
+    C, hidden, H, Hkv, d, ffn = 40, 64, 4, 4, 16, 96
+    wt = _weights(rng, hidden, H, Hkv, d, ffn, std=0.1)
+    x = orc.round_to_bf16(rng.standard_normal((C, hidden)))
+    rows = list(range(0, C, 3))
+    whole, _, _ = orc.decoder_layer(x, wt, H, Hkv, d, 0.25, 10000.0, 1e-6, rnd=orc.round_to_bf16)
+    y, _ = orc.decoder_layer_rows(x, wt, H, Hkv, d, 0.25, 10000.0, 1e-6, rows, rnd=orc.round_to_bf16)
+    diff = np.abs(y - whole[rows])
+    assert (diff > 0).mean() < 0.02
+    assert diff.max() <= 2.0 ** -6 * np.abs(whole).max()
