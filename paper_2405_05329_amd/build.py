@@ -17,10 +17,17 @@ SOURCES = ["kvra_api.hip", "kvra_append.hip", "kvra_attn.hip", "kvra_gemm.hip", 
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
-def build(verbose: bool = False, extra_flags=()) -> str:
+TRACE_LIB = os.path.join(PKG, "libkvra_trace.so")
+
+
+def build(verbose: bool = False, extra_flags=(), trace: bool = False) -> str:
+    """trace=True builds libkvra_trace.so instead: the same library with per-workgroup time stamps in the
+    attention kernel (-DKVRA_TRACE) and the kvra_trace_attach entry point, for timeline.py."""
     hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
     objs = []
-    bdir = os.path.join(PKG, "_build")
+    if trace:
+        extra_flags = tuple(extra_flags) + ("-DKVRA_TRACE",)
+    bdir = os.path.join(PKG, "_build_trace" if trace else "_build")
     os.makedirs(bdir, exist_ok=True)
     procs = []
     for src in SOURCES:
@@ -45,10 +52,11 @@ def build(verbose: bool = False, extra_flags=()) -> str:
             print(out)
     if failed:
         raise RuntimeError("hipcc failed")
-    cmd = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB, *objs]
+    lib = TRACE_LIB if trace else LIB
+    cmd = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", lib, *objs]
     subprocess.run(cmd, check=True)
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":
-    print(build(verbose="-v" in sys.argv))
+    print(build(verbose="-v" in sys.argv, trace="--trace" in sys.argv))

@@ -85,7 +85,23 @@ struct AttnArgs {
   int n_whole;       // workgroups [0, n_whole) take whole units
   int n_split;       // the next n_split units are cut into `segments` key segments each
   int segments;
+#ifdef KVRA_TRACE
+  unsigned long long* trace;   // kTraceWords words per workgroup, or nullptr
+#endif
 };
+
+#ifdef KVRA_TRACE
+// Timeline build (python -m paper_2405_05329_amd.build --trace): every workgroup leaves time stamps of the
+// constant 100 MHz clock - entry, first tile step, last tile step done, exit - with the compute unit it
+// ran on and its number of tile steps, for the accounting of where a launch's time goes.
+constexpr int kTraceWords = 8;
+__device__ __forceinline__ void trace_stamp(unsigned long long* rec, int word) {
+  if (rec != nullptr && threadIdx.x == 0) rec[word] = wall_clock64();
+}
+#define KVRA_TRACE_STAMP(rec, word) trace_stamp(rec, word)
+#else
+#define KVRA_TRACE_STAMP(rec, word)
+#endif
 
 // Work units of a launch.  Unit index u -> (kv head g, row tile qt), longest row tiles first; with
 // Hkv a multiple of 8 the heads are dealt to the 8 XCDs (workgroup ids go round-robin over XCDs,
@@ -141,7 +157,11 @@ __device__ __forceinline__ void lds_dma16_if(unsigned long long on_mask, const v
 // Otherwise the un-normalised state (O, m, l per lane) goes to partial for the fix-up kernel.
 template <int D>
 __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, const int g, const int qt,
-                                       const int jt0, const int jt1, float* partial) {
+                                       const int jt0, const int jt1, float* partial
+#ifdef KVRA_TRACE
+                                       , unsigned long long* trace_rec
+#endif
+                                       ) {
   constexpr int BN = key_tile(D);
   constexpr int MB = BN / 32;              // 32-key blocks of a tile
   constexpr int CPR = D / 8;               // 16-byte pieces per K/V row
@@ -309,6 +329,7 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, const int
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
   __syncthreads();
   if (!ONE_BARRIER && phase == 1) __syncthreads();   // second group runs one barrier behind the first
+  KVRA_TRACE_STAMP(trace_rec, 1);
 
   f32x16 s[MB];
   bf16x8 pf[MB][2];
@@ -493,6 +514,7 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, const int
   }
   static_assert(kStages == 3, "the unrolled loop above is written for a ring of three");
   if (!ONE_BARRIER && phase == 0) __syncthreads();   // both groups execute the same number of barriers
+  KVRA_TRACE_STAMP(trace_rec, 2);
 
   // ---- epilogue: O / l, bf16, store -----------------------------------------------------------
   if (partial != nullptr) {
@@ -527,19 +549,38 @@ template <int D>
 __global__ __launch_bounds__(kThreads, 1) void chunk_attn_kernel(AttnArgs a) {
   extern __shared__ u32x4 smem[];
   const int bid = blockIdx.x;
-  int g, qt;
+  int g, qt, jt0, jt1;
+  float* partial = nullptr;
   if (bid < a.n_whole) {
     unit_of(a, bid, &g, &qt);
-    attend<D>(a, smem, g, qt, 0, unit_steps(a, qt), nullptr);
-    return;
+    jt0 = 0;
+    jt1 = unit_steps(a, qt);
+  } else {
+    const int f = bid - a.n_whole;
+    const int seg = f / a.n_split, ui = f - seg * a.n_split;
+    unit_of(a, a.n_whole + ui, &g, &qt);
+    const long long n = unit_steps(a, qt);
+    jt0 = static_cast<int>(n * seg / a.segments);
+    jt1 = static_cast<int>(n * (seg + 1) / a.segments);
+    partial = a.scratch + static_cast<long long>(ui * a.segments + seg) * kPartialFloats(D);
   }
-  const int f = bid - a.n_whole;
-  const int seg = f / a.n_split, ui = f - seg * a.n_split;
-  unit_of(a, a.n_whole + ui, &g, &qt);
-  const long long n = unit_steps(a, qt);
-  const int jt0 = static_cast<int>(n * seg / a.segments), jt1 = static_cast<int>(n * (seg + 1) / a.segments);
-  float* partial = a.scratch + static_cast<long long>(ui * a.segments + seg) * kPartialFloats(D);
+#ifdef KVRA_TRACE
+  unsigned long long* rec = a.trace != nullptr ? a.trace + static_cast<long long>(bid) * kTraceWords : nullptr;
+  KVRA_TRACE_STAMP(rec, 0);
+  attend<D>(a, smem, g, qt, jt0, jt1, partial, rec);
+  KVRA_TRACE_STAMP(rec, 3);
+  if (rec != nullptr && threadIdx.x == 0) {
+    unsigned hw, xcc;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw));
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+    rec[4] = (static_cast<unsigned long long>(xcc) << 32) | hw;
+    rec[5] = static_cast<unsigned long long>(jt1 - jt0);
+    rec[6] = (static_cast<unsigned long long>(static_cast<unsigned>(g)) << 32) | static_cast<unsigned>(qt);
+    rec[7] = static_cast<unsigned long long>(jt0);
+  }
+#else
   attend<D>(a, smem, g, qt, jt0, jt1, partial);
+#endif
 }
 
 // Merges the key segments of every split unit: one single-wave workgroup per (unit, 32-row slice,
@@ -731,6 +772,13 @@ int plan_chunk_attn(int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_
 
 int64_t attn_static_scratch_bytes() { return static_cast<int64_t>(sizeof(scratch)); }
 
+#ifdef KVRA_TRACE
+namespace {
+unsigned long long* g_trace_buf = nullptr;
+long long g_trace_groups = 0;
+}  // namespace
+#endif
+
 int launch_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
                       int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_kv_heads, int head_dim,
                       float scale, void* out, hipStream_t stream, bool static_scratch_only) {
@@ -761,6 +809,9 @@ int launch_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
   a.n_whole = plan.whole_units;
   a.n_split = plan.split_units;
   a.segments = plan.segments;
+#ifdef KVRA_TRACE
+  a.trace = (a.n_whole + static_cast<long long>(a.n_split) * a.segments <= g_trace_groups) ? g_trace_buf : nullptr;
+#endif
   const unsigned smem = 2u * kStages * static_cast<unsigned>(a.bn) * static_cast<unsigned>(head_dim) * 2u;   // K ring + V ring
   const dim3 b3(kThreads);
   const dim3 g_main(static_cast<unsigned>(a.n_whole + static_cast<int64_t>(a.n_split) * a.segments));
@@ -773,3 +824,13 @@ int launch_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
 }
 
 }  // namespace kvra
+
+#ifdef KVRA_TRACE
+// Timeline build only: the device buffer (8 words of 8 bytes per workgroup) that the next kvra_chunk_attn
+// launches stamp; a launch with more workgroups than `workgroups` leaves no stamps.  NULL detaches.
+extern "C" int kvra_trace_attach(void* device_buffer, long long workgroups) {
+  kvra::g_trace_buf = static_cast<unsigned long long*>(device_buffer);
+  kvra::g_trace_groups = device_buffer != nullptr ? workgroups : 0;
+  return KVRA_OK;
+}
+#endif
