@@ -121,28 +121,56 @@ int kvra_chunk_attn_noalloc(const void* q, const void* k_cache, const void* v_ca
 int64_t kvra_chunk_attn_noalloc_scratch_bytes(void);
 
 /*
- * How kvra_chunk_attn cuts the chunk's trapezoid of (query, key) pairs (Fig. 2(c), Sec. 4.1) into
- * workgroups on a device with `n_cus` compute units.  Host arithmetic only: nothing is launched or
- * allocated, and no device needs to be present.  A unit is one kv head x one tile of
- * `rows_per_tile` query rows (row = token * group + head in group) walked over all the key tiles
- * it can see; `whole_units` run as one workgroup each; the `split_units` of a partly filled last
- * round are cut into `segments` equal key ranges, one workgroup each, whose partial results
- * (`scratch_bytes` of the per-device scratch) a second small kernel merges.  kvra_chunk_attn takes
- * this plan with the CU count of the current device (and the plain one, segments = 1, if the
- * scratch could not be allocated).
+ * How kvra_chunk_attn lays the chunk's trapezoid of (query, key) pairs (Fig. 2(c), Sec. 4.1) onto a device
+ * with `n_cus` compute units.  Host arithmetic only: nothing is launched or allocated, and no device
+ * needs to be present.
+ *   A unit is one kv head x one tile of `rows_per_tile` query rows (row = token * group + head in group)
+ * walked over all the key tiles it can see.  The kv heads are dealt to `groups` groups (8, one per XCD,
+ * when the head count and n_cus are multiples of 8; else 1); each group has `units` units, longest first,
+ * and `slots` persistent workgroups, one per compute unit: the launch has groups * slots workgroups.
+ *   In round 0 slot c runs unit c, but only its first `head_steps` key tiles if it is one of the `cut_units`
+ * longest units (units are cut while there are fewer than two complete rounds).  Rounds 1 .. rounds-1 are
+ * whole units.  The rest - the tails of the cut units, then the units beyond the complete rounds - is
+ * `segments` key ranges laid end to end and shared out among the slots so that all finish together after
+ * about `steps_per_slot` tile steps (five of which per piece are the allowance for starting and finishing it).
+ * `partial_pieces` pieces (over all groups) are not whole units: they leave their un-normalised results in
+ * the scratch (`scratch_bytes` = the partial-result slots the launch may touch x 132 KiB), and the piece
+ * of a unit that finishes last merges them inside the kernel.
+ *   kvra_chunk_attn takes this plan with the CU count of the current device; while it has no scratch (see
+ * the conventions at the top) it takes the plan in which no unit is cut.
  * Errors: KVRA_EINVAL (plan NULL, n_cus < 1, sizes as for kvra_chunk_attn), KVRA_EUNSUPPORTED.
  */
 typedef struct kvra_attn_plan {
   int row_tiles;        /* row tiles per kv head */
   int rows_per_tile;    /* multiple of 32, <= 256 */
   int key_tile;         /* keys per tile step: 64 at head_dim 128, 128 at head_dim 64 */
-  int whole_units;
-  int split_units;
-  int segments;         /* 1 = no key-split (then split_units = 0) */
+  int groups;
+  int slots;            /* per group */
+  int units;            /* per group */
+  int rounds;
+  int head_steps;
+  int cut_units;
+  int segments;
+  int steps_per_slot;
+  int partial_pieces;
   int64_t scratch_bytes;
 } kvra_attn_plan;
 int kvra_chunk_attn_plan(int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_kv_heads,
                          int head_dim, int n_cus, kvra_attn_plan* plan);
+
+/*
+ * The pieces of that plan, one record of 10 ints each, workgroup by workgroup in the order each
+ * workgroup runs them (host arithmetic only; the kernel walks the same list with the same code):
+ *   [0] workgroup id  [1] kv head  [2] row tile  [3] first key tile  [4] end key tile (exclusive)
+ *   [5] key tiles of the whole unit  [6] partial-result slot in the scratch, -1 for a whole unit
+ *   [7] number of pieces the merge of this unit reads, 0 for a whole unit  [8] 1 if this piece's slot is
+ *   among them  [9] index of the unit's merge counter, -1 for a whole unit
+ *   records    host array of capacity * 10 ints, or NULL with capacity 0 to ask for the count only
+ *   count_out  number of pieces of the launch (may exceed capacity; only `capacity` records are written)
+ * Errors: as kvra_chunk_attn_plan; KVRA_EINVAL for a negative capacity or NULL records with capacity > 0.
+ */
+int kvra_chunk_attn_pieces(int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_kv_heads,
+                           int head_dim, int n_cus, int32_t* records, int64_t capacity, int64_t* count_out);
 
 /*
  * Context-level load balancing (Sec. 4.2), host only.  Picks boundaries 0 = b_0 < b_1 < ... <

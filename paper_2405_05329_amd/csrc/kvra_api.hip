@@ -97,11 +97,29 @@ extern "C" int kvra_chunk_attn_plan(int64_t prefix_len, int64_t chunk_len, int n
   plan->row_tiles = p.row_tiles;
   plan->rows_per_tile = p.rows_per_tile;
   plan->key_tile = p.key_tile;
-  plan->whole_units = p.whole_units;
-  plan->split_units = p.split_units;
+  plan->groups = p.groups;
+  plan->slots = p.slots;
+  plan->units = p.units;
+  plan->rounds = p.rounds;
+  plan->head_steps = p.head_steps;
+  plan->cut_units = p.cut;
   plan->segments = p.segments;
-  plan->scratch_bytes = kvra::attn_partial_bytes(head_dim) * p.split_units * p.segments;
+  plan->steps_per_slot = p.steps_per_slot;
+  plan->partial_pieces = p.partial_pieces;
+  plan->scratch_bytes = kvra::attn_partial_bytes(128) * p.scratch_slots;
   return KVRA_OK;
+}
+
+extern "C" int kvra_chunk_attn_pieces(int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_kv_heads,
+                                      int head_dim, int n_cus, int32_t* records, int64_t capacity,
+                                      int64_t* count_out) {
+  if (n_cus < 1 || capacity < 0 || (records == nullptr && capacity > 0)) return KVRA_EINVAL;
+  if (chunk_len < 1 || prefix_len < 0) return KVRA_EINVAL;
+  int rc = check_heads(n_q_heads, n_kv_heads, head_dim);
+  if (rc != KVRA_OK) return rc;
+  if (chunk_len > kMaxTokens || prefix_len > kMaxTokens) return KVRA_EUNSUPPORTED;
+  return kvra::list_chunk_attn_pieces(prefix_len, chunk_len, n_q_heads, n_kv_heads, head_dim, n_cus, records,
+                                      capacity, count_out);
 }
 
 // ---------------------------------------------------------------- decoder layer around the attention

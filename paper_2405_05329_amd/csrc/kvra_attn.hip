@@ -43,6 +43,7 @@
 #include <algorithm>
 #include <mutex>
 #include <type_traits>
+#include <vector>
 
 namespace kvra {
 
@@ -80,14 +81,21 @@ struct AttnArgs {
   int rows_per_wg;   // virtual rows per workgroup: 32 * (active waves), <= 256
   float c_log2;      // scale * log2(e): softmax runs in base 2
   int bn;            // keys per tile, key_tile(head_dim)
-  // key-split launches only
-  float* scratch;    // partial results, one slot per (split unit, key segment)
-  int n_whole;       // workgroups [0, n_whole) take whole units
-  int n_split;       // the next n_split units are cut into `segments` key segments each
+  // schedule (see AttnPlan): the launch has groups * slots persistent workgroups
+  int groups;
+  int slots;
+  int units;         // per group
+  int rounds;
+  int head_steps;
+  int cut;
   int segments;
+  float* scratch;    // partial results: slots_per_group() slots per group; nullptr when nothing is cut
+  int* counters;     // key tiles merged so far, one per (group, segment); all zero between launches
 #ifdef KVRA_TRACE
-  unsigned long long* trace;   // kTraceWords words per workgroup, or nullptr
+  unsigned long long* trace;   // kTraceWords words per piece, kTracePieces pieces per workgroup, or nullptr
 #endif
+  unsigned fill_seg[kMaxSlots + 1];
+  unsigned fill_off[kMaxSlots + 1];
 };
 
 #ifdef KVRA_TRACE
@@ -95,6 +103,7 @@ struct AttnArgs {
 // constant 100 MHz clock - entry, first tile step, last tile step done, exit - with the compute unit it
 // ran on and its number of tile steps, for the accounting of where a launch's time goes.
 constexpr int kTraceWords = 8;
+constexpr int kTracePieces = 8;   // pieces of a workgroup that leave stamps
 __device__ __forceinline__ void trace_stamp(unsigned long long* rec, int word) {
   if (rec != nullptr && threadIdx.x == 0) rec[word] = wall_clock64();
 }
@@ -103,25 +112,114 @@ __device__ __forceinline__ void trace_stamp(unsigned long long* rec, int word) {
 #define KVRA_TRACE_STAMP(rec, word)
 #endif
 
-// Work units of a launch.  Unit index u -> (kv head g, row tile qt), longest row tiles first; with
-// Hkv a multiple of 8 the heads are dealt to the 8 XCDs (workgroup ids go round-robin over XCDs,
-// and a workgroup's unit index has its own id's low three bits) so that each XCD's L2 holds the
-// K/V stream of its own heads only.
-__device__ __forceinline__ void unit_of(const AttnArgs& a, int u, int* g, int* qt) {
-  if ((a.Hkv & 7) == 0) {
-    const int xcd = u & 7, j = u >> 3, hp = a.Hkv >> 3;
-    *g = xcd + 8 * (j % hp);
-    *qt = a.nq_tiles - 1 - j / hp;
-  } else {
-    *g = u % a.Hkv;
-    *qt = a.nq_tiles - 1 - u / a.Hkv;
+// Units of a group, longest row tiles first: unit j of group x is kv head x + groups * (j % hp),
+// hp = heads per group, row tile nq_tiles - 1 - j / hp.  With 8 groups, workgroup ids go round-robin
+// over the XCDs, so group x = workgroup id % 8 lives on one XCD and that XCD's L2 holds the K/V
+// stream of its own heads only.
+__host__ __device__ __forceinline__ void unit_of(const AttnArgs& a, int x, int j, int* g, int* qt) {
+  const int hp = a.Hkv / a.groups;
+#ifdef KVRA_HEADS_CONTIGUOUS
+  *g = x * hp + (j % hp);
+#else
+  *g = x + a.groups * (j % hp);
+#endif
+  *qt = a.nq_tiles - 1 - j / hp;
+}
+__host__ __device__ __forceinline__ int unit_steps(const AttnArgs& a, int qt) {
+  const int rows = a.chunk * a.G;
+  const int row_hi = (qt + 1) * a.rows_per_wg < rows ? (qt + 1) * a.rows_per_wg : rows;   // exclusive, in virtual rows
+  return (a.prefix + (row_hi - 1) / a.G) / a.bn + 1;                                      // key tiles the row tile walks
+}
+// Partial-result slots of a group: id c + s for the piece of segment s that slot c runs (both only grow
+// along the line of segments, so the sum is unique), and slots + segments + s for the head of unit s.
+__host__ __device__ __forceinline__ int slots_per_group(const AttnArgs& a) { return a.slots + 2 * a.segments; }
+
+// One piece of work: key tiles [jt0, jt1) of a unit.
+struct Piece {
+  int g, qt;         // kv head, row tile
+  int jt0, jt1;
+  int n;             // key tiles of the whole unit
+  int seg;           // segment the unit belongs to (pieces that are not the whole unit), else -1
+  int slot;          // partial-result slot within the group, -1 for a whole unit
+};
+
+// The pieces of slot c of group x, in the order the slot runs them (the same code on the device, where
+// the kernel walks them, and on the host, where kvra_chunk_attn_pieces lists them).
+struct PieceWalker {
+  int x, c, seg, off, seg_end, off_end, round;
+  __host__ __device__ PieceWalker(const AttnArgs& a, int group, int slot)
+      : x(group), c(slot), seg(static_cast<int>(a.fill_seg[slot])), off(static_cast<int>(a.fill_off[slot])),
+        seg_end(static_cast<int>(a.fill_seg[slot + 1])), off_end(static_cast<int>(a.fill_off[slot + 1])), round(0) {}
+  __host__ __device__ bool next(const AttnArgs& a, Piece* pc) {
+    const int P = a.slots;
+    if (round == 0 && c < a.units) {
+      // first round: unit c, cut after head_steps key tiles if it is one of the `cut` longest units
+      ++round;
+      unit_of(a, x, c, &pc->g, &pc->qt);
+      pc->n = unit_steps(a, pc->qt);
+      pc->jt0 = 0;
+      const bool is_cut = c < a.cut;
+      pc->jt1 = is_cut ? a.head_steps : pc->n;
+      pc->seg = is_cut ? c : -1;
+      pc->slot = is_cut ? P + a.segments + c : -1;
+      return true;
+    }
+    if (round > 0 && round < a.rounds) {
+      const int j = round * P + ((round & 1) ? P - 1 - c : c);
+      ++round;
+      unit_of(a, x, j, &pc->g, &pc->qt);
+      pc->n = unit_steps(a, pc->qt);
+      pc->jt0 = 0;
+      pc->jt1 = pc->n;
+      pc->seg = -1;
+      pc->slot = -1;
+      return true;
+    }
+    if (seg < seg_end || (seg == seg_end && off < off_end)) {
+      round = a.rounds + 1;
+      // the unit behind segment `seg` and where the segment starts inside it: the tails of the cut units
+      // come first, then the units beyond the complete rounds
+      const int j = seg < a.cut ? seg : a.rounds * P + seg - a.cut;
+      const int first = seg < a.cut ? a.head_steps : 0;
+      unit_of(a, x, j, &pc->g, &pc->qt);
+      pc->n = unit_steps(a, pc->qt);
+      pc->jt0 = first + off;
+      pc->jt1 = seg < seg_end ? pc->n : first + off_end;
+      const bool whole = pc->jt0 == 0 && pc->jt1 == pc->n;
+      pc->seg = whole ? -1 : seg;
+      pc->slot = whole ? -1 : c + seg;
+      if (seg < seg_end) { ++seg; off = 0; }
+      else off = off_end;
+      return true;
+    }
+    return false;
+  }
+};
+
+// The partial-result slots (within the group) of all pieces of segment s, in the fixed order of the merge:
+// the head (if the segment is the tail of a cut unit), then the slots whose share of the line of segments
+// meets this segment.
+template <typename F>
+__host__ __device__ __forceinline__ void for_each_piece_of_segment(const AttnArgs& a, int s, F&& fn) {
+  if (s < a.cut) fn(a.slots + a.segments + s);
+  for (int c = 0; c < a.slots; ++c) {
+    const unsigned s0 = a.fill_seg[c], o0 = a.fill_off[c], s1 = a.fill_seg[c + 1], o1 = a.fill_off[c + 1];
+    const bool nonempty = s0 < s1 || (s0 == s1 && o0 < o1);
+    const bool meets = static_cast<int>(s0) <= s && (static_cast<int>(s1) > s || (static_cast<int>(s1) == s && o1 > 0));
+    if (nonempty && meets) fn(c + s);
   }
 }
-__device__ __forceinline__ int unit_steps(const AttnArgs& a, int qt) {
-  const int row_hi = min((qt + 1) * a.rows_per_wg, a.chunk * a.G);   // exclusive, in virtual rows
-  return (a.prefix + (row_hi - 1) / a.G) / a.bn + 1;                 // key tiles the row tile walks
-}
+
 constexpr int kPartialFloats(int D) { return kWaves * (D / 32 * 16 + 2) * 64; }   // per scratch slot
+
+// A store that is visible to the whole device once it has been acknowledged, and a load that sees such
+// stores (they go past whatever a non-coherent cache level holds).
+__device__ __forceinline__ void store_coherent(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float load_coherent(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
 __device__ __forceinline__ float other_half(float x) {
   // value held by lane ^ 32
@@ -152,16 +250,18 @@ __device__ __forceinline__ void lds_dma16_if(unsigned long long on_mask, const v
                : "memory", "m0", "scc");
 }
 
-// One fragment of work: the queries of row tile qt of kv head g against key tiles [jt0, jt1).
-// partial == nullptr: the fragment covers all the keys the tile needs, O / l goes to a.out.
-// Otherwise the un-normalised state (O, m, l per lane) goes to partial for the fix-up kernel.
+// One piece of work: the queries of row tile pc.qt of kv head pc.g against key tiles [pc.jt0, pc.jt1).
+// pc.slot < 0: the piece covers all the keys the tile needs, O / l goes to a.out.  Otherwise the
+// un-normalised state (O, m, l per lane) goes to the piece's partial-result slot of group x, and the piece
+// of the unit that gets there last merges all of them (in a fixed order, so that the result does not depend
+// on which one that was) and writes the output.
 template <int D>
-__device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, const int g, const int qt,
-                                       const int jt0, const int jt1, float* partial
+__device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, int* last_flag, const int x, const Piece& pc
 #ifdef KVRA_TRACE
                                        , unsigned long long* trace_rec
 #endif
                                        ) {
+  const int g = pc.g, qt = pc.qt, jt0 = pc.jt0, jt1 = pc.jt1;
   constexpr int BN = key_tile(D);
   constexpr int MB = BN / 32;              // 32-key blocks of a tile
   constexpr int CPR = D / 8;               // 16-byte pieces per K/V row
@@ -517,16 +617,81 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, const int
   KVRA_TRACE_STAMP(trace_rec, 2);
 
   // ---- epilogue: O / l, bf16, store -----------------------------------------------------------
-  if (partial != nullptr) {
-    // [wave][register][lane]: every store is 256 consecutive bytes per wave
-    float* p = partial + (wave * (DB * 16 + 2)) * 64 + lane;
+  if (pc.slot >= 0) {
+    // [wave][register][lane]: every store is 256 consecutive bytes per wave.  The pieces of a unit are
+    // handed from workgroup to workgroup without a fence (a device-scope fence writes back and invalidates
+    // the whole L2 of the XCD: tens of microseconds, and the K/V stream the other workgroups share is
+    // gone): the partial results are written with device-coherent stores, the wave waits until all of
+    // them have been acknowledged, and only then, after a workgroup barrier, are the unit's key tiles
+    // added to its counter; the piece that completes the count reads the others with device-coherent loads.
+    constexpr int WAVE_FLOATS = (DB * 16 + 2) * 64;
+    float* group_slots = a.scratch + static_cast<long long>(x) * slots_per_group(a) * kPartialFloats(D);
+    {
+      float* p = group_slots + static_cast<long long>(pc.slot) * kPartialFloats(D) + wave * WAVE_FLOATS + lane;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) store_coherent(p + (db * 16 + e) * 64, o[db][e]);
+      store_coherent(p + (DB * 16) * 64, m);
+      store_coherent(p + (DB * 16 + 1) * 64, l);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    int* counter = a.counters + x * kMaxSlots + pc.seg;
+    if (tid == 0) {
+      const int before = atomicAdd(counter, nt);
+      *last_flag = (before + nt == pc.n) ? 1 : 0;
+    }
+    __syncthreads();
+    const bool last = *last_flag != 0;
+    __syncthreads();                       // the flag may be rewritten by the next piece
+    if (!last) return;
+    if (tid == 0) *counter = 0;            // ready for the next launch
+    // The unit's pieces in their fixed order (the head if the segment is the tail of a cut unit, then the
+    // slots whose share of the line of segments meets it), merged one after the other into (O, m, l)
+    // starting from nothing: the result does not depend on which piece happened to be the last.
+    // Which slots: every lane tests four slots of the table, the wave votes.
+    const float* mine = group_slots + wave * WAVE_FLOATS + lane;
+    m = kNoKeyYet;
+    l = 0.0f;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) p[(db * 16 + e) * 64] = o[db][e];
-    p[(DB * 16) * 64] = m;
-    p[(DB * 16 + 1) * 64] = l;
-    return;
+      for (int e = 0; e < 16; ++e) o[db][e] = 0.0f;
+    auto merge_in = [&](int slot) {
+      const float* p = mine + static_cast<long long>(slot) * kPartialFloats(D);
+      float po[DB * 16];
+#pragma unroll
+      for (int i = 0; i < DB * 16; ++i) po[i] = load_coherent(p + i * 64);
+      const float pm = load_coherent(p + (DB * 16) * 64), pl = load_coherent(p + (DB * 16 + 1) * 64);
+      const float mn = fmaxf(m, pm);
+      const float wa = __builtin_amdgcn_exp2f(m - mn), wb = __builtin_amdgcn_exp2f(pm - mn);
+      m = mn;
+      l = fmaf(pl, wb, l * wa);
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o[db][e] = fmaf(po[db * 16 + e], wb, o[db][e] * wa);
+    };
+    if (pc.seg < a.cut) merge_in(a.slots + a.segments + pc.seg);
+    static_assert(kMaxSlots <= 256, "four votes of 64 lanes cover the table");
+    for (int k = 0; k < 4; ++k) {
+      const int c = 64 * k + lane;
+      bool meets = false;
+      if (c < a.slots) {
+        const unsigned s0 = a.fill_seg[c], o0 = a.fill_off[c], s1 = a.fill_seg[c + 1], o1 = a.fill_off[c + 1];
+        const bool nonempty = s0 < s1 || (s0 == s1 && o0 < o1);
+        meets = nonempty && static_cast<int>(s0) <= pc.seg &&
+                (static_cast<int>(s1) > pc.seg || (static_cast<int>(s1) == pc.seg && o1 > 0));
+      }
+      unsigned long long votes = __builtin_amdgcn_ballot_w64(meets);
+      while (votes != 0) {
+        const int c_meet = 64 * k + __builtin_ctzll(votes);
+        votes &= votes - 1;
+        merge_in(c_meet + pc.seg);
+      }
+      if (64 * (k + 1) >= a.slots) break;
+    }
   }
   const float lsum = l + other_half(l);
   if (wave_active && row_valid) {
@@ -544,100 +709,49 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, const int
   }
 }
 
-// One workgroup per whole unit, then one per key segment of the split units (segment-major).
+// Persistent workgroups: workgroup id -> (group x, slot c); the slot walks its pieces in the order of the
+// schedule (whole units of the complete rounds, or the head of its own unit; then its share of the line
+// of segments).
 template <int D>
 __global__ __launch_bounds__(kThreads, 1) void chunk_attn_kernel(AttnArgs a) {
   extern __shared__ u32x4 smem[];
-  const int bid = blockIdx.x;
-  int g, qt, jt0, jt1;
-  float* partial = nullptr;
-  if (bid < a.n_whole) {
-    unit_of(a, bid, &g, &qt);
-    jt0 = 0;
-    jt1 = unit_steps(a, qt);
-  } else {
-    const int f = bid - a.n_whole;
-    const int seg = f / a.n_split, ui = f - seg * a.n_split;
-    unit_of(a, a.n_whole + ui, &g, &qt);
-    const long long n = unit_steps(a, qt);
-    jt0 = static_cast<int>(n * seg / a.segments);
-    jt1 = static_cast<int>(n * (seg + 1) / a.segments);
-    partial = a.scratch + static_cast<long long>(ui * a.segments + seg) * kPartialFloats(D);
-  }
+  __shared__ int last_flag;
+  const int x = blockIdx.x % a.groups, c = blockIdx.x / a.groups;
+  PieceWalker walker(a, x, c);
 #ifdef KVRA_TRACE
-  unsigned long long* rec = a.trace != nullptr ? a.trace + static_cast<long long>(bid) * kTraceWords : nullptr;
-  KVRA_TRACE_STAMP(rec, 0);
-  attend<D>(a, smem, g, qt, jt0, jt1, partial, rec);
-  KVRA_TRACE_STAMP(rec, 3);
-  if (rec != nullptr && threadIdx.x == 0) {
-    unsigned hw, xcc;
-    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw));
-    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
-    rec[4] = (static_cast<unsigned long long>(xcc) << 32) | hw;
-    rec[5] = static_cast<unsigned long long>(jt1 - jt0);
-    rec[6] = (static_cast<unsigned long long>(static_cast<unsigned>(g)) << 32) | static_cast<unsigned>(qt);
-    rec[7] = static_cast<unsigned long long>(jt0);
-  }
-#else
-  attend<D>(a, smem, g, qt, jt0, jt1, partial);
+  int ordinal = 0;
 #endif
-}
-
-// Merges the key segments of every split unit: one single-wave workgroup per (unit, 32-row slice,
-// 32-wide block of d), lanes as in the main kernel.
-template <int D>
-__global__ __launch_bounds__(64) void chunk_attn_fixup_kernel(AttnArgs a) {
-  constexpr int DB = D / 32;
-  const int db = blockIdx.x % DB, wave = (blockIdx.x / DB) % kWaves, ui = blockIdx.x / (DB * kWaves);
-  int g, qt;
-  unit_of(a, a.n_whole + ui, &g, &qt);
-  const int lane = threadIdx.x;
-  const int nn = lane & 31, kg = lane >> 5;
-  const int VR = a.chunk * a.G;
-  const int row_lo = qt * a.rows_per_wg;
-  const int row_hi = min(row_lo + a.rows_per_wg, VR);
-  const int vr = row_lo + wave * 32 + nn;
-  if (row_lo + wave * 32 >= row_hi) return;   // slice beyond the tile (wave-uniform)
-
-  // exponent references first: the merged one is their maximum
-  const float* base = a.scratch + static_cast<long long>(ui * a.segments) * kPartialFloats(D) +
-                      (wave * (DB * 16 + 2)) * 64 + lane;
-  float m = kNoKeyYet;
-  for (int seg = 0; seg < a.segments; ++seg)
-    m = fmaxf(m, base[static_cast<long long>(seg) * kPartialFloats(D) + (DB * 16) * 64]);
-  float o[16];
-#pragma unroll
-  for (int e = 0; e < 16; ++e) o[e] = 0.0f;
-  float l = 0.0f;
-  for (int seg = 0; seg < a.segments; ++seg) {
-    const float* p = base + static_cast<long long>(seg) * kPartialFloats(D);
-    const float w = __builtin_amdgcn_exp2f(p[(DB * 16) * 64] - m);
-    l = fmaf(p[(DB * 16 + 1) * 64], w, l);
-#pragma unroll
-    for (int e = 0; e < 16; ++e) o[e] = fmaf(p[(db * 16 + e) * 64], w, o[e]);
-  }
-  const float lsum = l + other_half(l);
-  if (vr < row_hi) {
-    const int r = vr / a.G;
-    const int h = g * a.G + (vr - r * a.G);
-    const float inv = 1.0f / lsum;
-    __bf16* orow = a.out + (static_cast<long long>(r) * a.H + h) * D;
-#pragma unroll
-    for (int r4 = 0; r4 < 4; ++r4) {
-      bf16x4 w4;
-#pragma unroll
-      for (int t = 0; t < 4; ++t) w4[t] = static_cast<__bf16>(o[4 * r4 + t] * inv);
-      *reinterpret_cast<bf16x4*>(orow + 32 * db + 8 * r4 + 4 * kg) = w4;
+  Piece pc;
+  while (walker.next(a, &pc)) {
+#ifdef KVRA_TRACE
+    unsigned long long* rec = (a.trace != nullptr && ordinal < kTracePieces)
+        ? a.trace + (static_cast<long long>(blockIdx.x) * kTracePieces + ordinal) * kTraceWords : nullptr;
+    ++ordinal;
+    KVRA_TRACE_STAMP(rec, 0);
+    attend<D>(a, smem, &last_flag, x, pc, rec);
+    KVRA_TRACE_STAMP(rec, 3);
+    if (rec != nullptr && threadIdx.x == 0) {
+      unsigned hw, xcc;
+      asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw));
+      asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+      rec[4] = (static_cast<unsigned long long>(xcc) << 32) | hw;
+      rec[5] = static_cast<unsigned long long>(pc.jt1 - pc.jt0);
+      rec[6] = (static_cast<unsigned long long>(static_cast<unsigned>(pc.g)) << 32) | static_cast<unsigned>(pc.qt);
+      rec[7] = (static_cast<unsigned long long>(static_cast<unsigned>(pc.slot + 1)) << 32) | static_cast<unsigned>(pc.jt0);
     }
+#else
+    attend<D>(a, smem, &last_flag, x, pc);
+#endif
   }
 }
 
 namespace {
 
-// Per-device scratch of the key-split path: kSlotsPerCu partial-result slots per CU (192 units on
-// 256 CUs need four pieces per unit to gain anything), allocated on first use and kept until the
-// process ends.
+// Scratch of the merge path: partial-result slots (three per CU cover every schedule: a group touches at
+// most slots + 2 * segments of them, segments < slots) followed by the merge counters.  The allocated one
+// is per device, taken on first use and kept until the process ends.
 constexpr int kSlotsPerCu = 3;
+constexpr int kCounterInts = 8 * kMaxSlots;
 constexpr int kMaxDevices = 16;
 float* g_scratch[kMaxDevices] = {};
 int g_cus[kMaxDevices] = {};
@@ -652,17 +766,20 @@ int device_cus(int dev) {
   return g_cus[dev];
 }
 
-// The allocated scratch of the current device, or nullptr (the caller then launches without key-split).
-// A failed attempt is not remembered: a call made while `stream` is being captured (an allocation
-// would be illegal there) or while memory is short runs unsplit, and a later call tries again.
-float* device_scratch(hipStream_t stream, int* cus_out) {
+// The allocated scratch of the current device, or nullptr (the caller then launches without cutting
+// units).  A failed attempt is not remembered: a call made while `stream` is being captured (an
+// allocation would be illegal there) or while memory is short runs uncut, and a later call tries again.
+float* device_scratch(hipStream_t stream, int* cus_out, int64_t* slots_out) {
   *cus_out = 0;
+  *slots_out = 0;
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
   std::lock_guard<std::mutex> lock(g_scratch_mutex);
   const int cus = device_cus(dev);
   *cus_out = cus;
   if (cus <= 0) return nullptr;
+  const int64_t slots = static_cast<int64_t>(kSlotsPerCu) * cus;
+  *slots_out = slots;
   if (g_scratch[dev] == nullptr) {
     hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
     if (hipStreamIsCapturing(stream, &capturing) != hipSuccess) {
@@ -670,10 +787,19 @@ float* device_scratch(hipStream_t stream, int* cus_out) {
       return nullptr;
     }
     if (capturing != hipStreamCaptureStatusNone) return nullptr;
-    const size_t bytes = static_cast<size_t>(kSlotsPerCu) * cus * kPartialFloats(128) * sizeof(float);
+    const size_t slot_bytes = static_cast<size_t>(slots) * kPartialFloats(128) * sizeof(float);
     void* p = nullptr;
-    if (hipMalloc(&p, bytes) == hipSuccess) g_scratch[dev] = static_cast<float*>(p);
-    else (void)hipGetLastError();   // leave no sticky error behind; the plain launch needs no scratch
+    if (hipMalloc(&p, slot_bytes + kCounterInts * sizeof(int)) != hipSuccess) {
+      (void)hipGetLastError();   // leave no sticky error behind; the uncut launch needs no scratch
+      return nullptr;
+    }
+    // the counters start at zero and every merge puts its counter back to zero
+    if (hipMemset(static_cast<char*>(p) + slot_bytes, 0, kCounterInts * sizeof(int)) != hipSuccess) {
+      (void)hipGetLastError();
+      (void)hipFree(p);
+      return nullptr;
+    }
+    g_scratch[dev] = static_cast<float*>(p);
   }
   return g_scratch[dev];
 }
@@ -682,12 +808,13 @@ float* device_scratch(hipStream_t stream, int* cus_out) {
 
 // ---- scratch of kvra_chunk_attn_noalloc: a fixed array in the library's device image ------------
 // kStaticSlots partial-result slots = 3 per CU of a 256-CU device (what the allocating path takes
-// there, so that both entry points cut a launch the same way).  Every device the library runs on
+// there, so that both entry points cut a launch the same way), then the merge counters (zero like
+// every static array, and put back to zero by every merge).  Every device the library runs on
 // holds its own copy at its own address for the life of the process.  In host code the array's
 // name is only a handle for hipGetSymbolAddress: the device address is asked for once per device,
 // with that device current, and that pointer is what the kernels get.
 constexpr int kStaticSlots = 768;
-static __device__ __align__(256) float scratch[static_cast<size_t>(kStaticSlots) * kPartialFloats(128)];
+static __device__ __align__(256) float scratch[static_cast<size_t>(kStaticSlots) * kPartialFloats(128) + kCounterInts];
 
 namespace {
 
@@ -711,20 +838,63 @@ float* static_scratch(int* cus_out) {
   return g_static_scratch[dev];
 }
 
+// ---- the schedule (host arithmetic) --------------------------------------------------------------
+#ifndef KVRA_ALLOWANCE
+#define KVRA_ALLOWANCE 5
+#endif
+#ifndef KVRA_MINPIECE
+#define KVRA_MINPIECE 8
+#endif
+#ifndef KVRA_CUT_ROUNDS
+#define KVRA_CUT_ROUNDS 1
+#endif
+constexpr int kPieceAllowance = KVRA_ALLOWANCE;   // what starting and finishing a piece costs, in tile steps
+constexpr int kMinPiece = KVRA_MINPIECE;          // no piece shorter than this many tile steps is cut off a unit
+
+// Shares the line of segments out to the slots so that every slot's load (what it already has plus its
+// share plus one allowance per share) stays within `target`; returns whether the whole line was placed.
+// seg_len[s]: length of segment s, the first cut_tails of them tails of cut units; load[c]: tile steps
+// (with allowances) slot c runs before its share.
+// Cuts never leave less than kMinPiece steps of a segment on either side; with whole_segments_only no
+// segment is cut at all.
+bool share_out(const std::vector<int>& seg_len, const std::vector<int64_t>& load, int64_t target,
+               bool whole_segments_only, int cut_tails, unsigned* fill_seg, unsigned* fill_off, int* partial_pieces) {
+  const int P = static_cast<int>(load.size()), S = static_cast<int>(seg_len.size());
+  int seg = 0, off = 0, partial = 0;
+  for (int c = 0; c < P; ++c) {
+    fill_seg[c] = static_cast<unsigned>(seg);
+    fill_off[c] = static_cast<unsigned>(off);
+    int64_t room = target - load[c];
+    while (seg < S) {
+      room -= kPieceAllowance;                       // every piece of the share pays the allowance
+      if (room <= 0) break;
+      const int left = seg_len[seg] - off;           // what is left of this segment
+      if (room >= left || (!whole_segments_only && left - room < kMinPiece && room + kMinPiece > left)) {
+        // take the rest of the segment (going over the target by less than kMinPiece is allowed)
+        if (off > 0 || seg < cut_tails) ++partial;   // (the tail of a cut unit is never a whole unit)
+        room -= left;
+        ++seg;
+        off = 0;
+      } else {
+        if (whole_segments_only || room < kMinPiece) break;
+        off += static_cast<int>(room);
+        ++partial;
+        break;
+      }
+    }
+  }
+  fill_seg[P] = static_cast<unsigned>(seg);
+  fill_off[P] = static_cast<unsigned>(off);
+  *partial_pieces = partial;
+  return seg == S;
+}
+
 }  // namespace
 
-// Shape of a kvra_chunk_attn launch on a device with `cus` compute units, scratch permitting
-// (host arithmetic only).  Normally one workgroup per unit, every unit whole.  Key-split launch: the
-// units beyond the last full round of CUs (all of them when there are fewer units than CUs) are cut
-// into S key segments each.  Time of that last round in units of a whole row tile: 1 without the
-// split, t(S) = ceil(rest * S / CUs) / S with it.  Feasible S: one scratch slot per piece
-// (kSlotsPerCu per CU) and at least kMinSteps key tiles per piece.  Taken: the smallest S that brings
-// the whole launch (full rounds + t) within 12 % of the best feasible one, if its t is at most 0.7.
-// (A partly filled chip clocks higher, and pieces cost a fix-up pass: on 256 CUs 192 units run
-// faster whole than as 768 quarter pieces in three rounds, t = 0.75.)
 int64_t attn_partial_bytes(int head_dim) {
   return static_cast<int64_t>(head_dim == 128 ? kPartialFloats(128) : kPartialFloats(64)) * sizeof(float);
 }
+int64_t attn_counter_bytes() { return static_cast<int64_t>(kCounterInts) * sizeof(int); }
 
 int plan_chunk_attn(int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_kv_heads, int head_dim,
                     int cus, bool scratch_available, AttnPlan* plan) {
@@ -735,42 +905,80 @@ int plan_chunk_attn(int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_
   const int64_t slices = (vrows + 31) / 32;
   const int64_t tiles = (slices + kWaves - 1) / kWaves;
   const int64_t slices_per_tile = (slices + tiles - 1) / tiles;
-  const int64_t units = tiles * n_kv_heads;
-  if (units > 0x7FFFFFFF) return KVRA_EUNSUPPORTED;
-  plan->row_tiles = static_cast<int>(tiles);
-  plan->rows_per_tile = static_cast<int>(32 * slices_per_tile);
-  plan->key_tile = key_tile(head_dim);
-  plan->whole_units = static_cast<int>(units);
-  plan->split_units = 0;
-  plan->segments = 1;
-  if (!scratch_available || cus <= 0) return KVRA_OK;
+  if (tiles * n_kv_heads > 0x3FFFFFFF) return KVRA_EUNSUPPORTED;
+  const int bn = key_tile(head_dim);
+  const int rows_per_tile = static_cast<int>(32 * slices_per_tile);
+  const int R = static_cast<int>(tiles);
+  if (cus < 1) cus = 1;
+  const int groups = (n_kv_heads % 8 == 0 && cus % 8 == 0) ? 8 : 1;
+  const int P = std::min(cus / groups, kMaxSlots);
+  const int hp = n_kv_heads / groups;
+  const int64_t U64 = static_cast<int64_t>(R) * hp;
+  const int U = static_cast<int>(U64);
+  auto steps_of_tile = [&](int qt) -> int {
+    const int64_t row_hi = std::min<int64_t>(static_cast<int64_t>(qt + 1) * rows_per_tile, vrows);
+    return static_cast<int>((prefix_len + (row_hi - 1) / G) / bn + 1);
+  };
+  auto steps_of_unit = [&](int j) -> int { return steps_of_tile(R - 1 - j / hp); };
 
-  constexpr int kMinSteps = 16, kMaxSegments = 16;
-  const int64_t rest = units % cus;
-  if (rest == 0) return KVRA_OK;
-  // shortest split unit = the last row tile
-  const int64_t last_rows = std::min<int64_t>(plan->rows_per_tile, vrows);
-  const int64_t min_steps = (prefix_len + (last_rows - 1) / G) / plan->key_tile + 1;
-  double t[kMaxSegments + 1], t_min = 1.0;
-  int s_max = 1, best = 1;
-  for (int S = 2; S <= kMaxSegments; ++S) {
-    if (rest * S > kSlotsPerCu * static_cast<int64_t>(cus) || min_steps / S < kMinSteps) break;
-    t[S] = static_cast<double>((rest * S + cus - 1) / cus) / S;
-    t_min = std::min(t_min, t[S]);
-    s_max = S;
+  plan->row_tiles = R;
+  plan->rows_per_tile = rows_per_tile;
+  plan->key_tile = bn;
+  plan->groups = groups;
+  plan->slots = P;
+  plan->units = U;
+  plan->rounds = U / P;
+  std::vector<int> n(U);
+  for (int j = 0; j < U; ++j) n[j] = steps_of_unit(j);
+  const int first_round = std::min(U, P);         // units of the first round: unit c on slot c
+  // Cutting the first round's units pays while a slot runs at most one more unit after it; with more
+  // rounds the reverse order of every second round evens the loads out and the leftover units do the rest.
+  const bool may_cut = scratch_available && plan->rounds <= KVRA_CUT_ROUNDS && n[0] >= 2 * kMinPiece;
+  // load of every slot from the rounds after the first (every second round in reverse slot order)
+  std::vector<int64_t> later(P, 0), load(P, 0);
+  for (int k = 1; k < plan->rounds; ++k)
+    for (int c = 0; c < P; ++c) later[c] += n[k * P + ((k & 1) ? P - 1 - c : c)] + kPieceAllowance;
+  std::vector<int> seg_len;
+  int partial = 0, cut = 0;
+  // For a finishing time `target`: cut the first round's units at head = target - allowance (if allowed),
+  // line up their tails and the leftover units, share the line out; true if everything fits.
+  auto fits = [&](int64_t target) -> bool {
+    const int64_t head = target - kPieceAllowance;
+    seg_len.clear();
+    cut = 0;
+    if (may_cut)
+      while (cut < first_round && n[cut] >= head + kMinPiece && head >= kMinPiece) {
+        seg_len.push_back(n[cut] - static_cast<int>(head));
+        ++cut;
+      }
+    for (int j = std::max(plan->rounds, 1) * P; j < U; ++j) seg_len.push_back(n[j]);
+    for (int c = 0; c < P; ++c)
+      load[c] = later[c] + (c < first_round ? (c < cut ? head : n[c]) + kPieceAllowance : 0);
+    // (a unit whose tail would be shorter than the minimum piece stays whole and may overshoot by that much)
+    for (int c = 0; c < P; ++c)
+      if (load[c] >= target + (c < first_round && may_cut ? kMinPiece : 1)) return false;
+    return share_out(seg_len, load, target, !scratch_available, cut, plan->fill_seg, plan->fill_off, &partial);
+  };
+  int64_t total = 0;
+  for (int j = 0; j < U; ++j) total += n[j] + kPieceAllowance;
+  int64_t lo = 0, hi = total + kPieceAllowance + 1;           // everything on one slot: always enough
+  while (lo + 1 < hi) {                                       // smallest finishing time that fits
+    const int64_t mid = (lo + hi) / 2;
+    if (fits(mid)) hi = mid;
+    else lo = mid;
   }
-  const double full_rounds = static_cast<double>(units / cus);
-  for (int S = 2; S <= s_max; ++S)
-    if (t[S] <= 0.7 && full_rounds + t[S] <= 1.12 * (full_rounds + t_min)) { best = S; break; }
-  if (best > 1) {
-    plan->whole_units = static_cast<int>(units - rest);
-    plan->split_units = static_cast<int>(rest);
-    plan->segments = best;
-  }
+  fits(hi);
+  plan->head_steps = cut > 0 ? static_cast<int>(hi - kPieceAllowance) : 0;
+  plan->cut = cut;
+  plan->segments = static_cast<int>(seg_len.size());
+  plan->steps_per_slot = static_cast<int>(hi);
+  partial += cut;                                             // the heads of the cut units
+  plan->partial_pieces = partial * groups;
+  plan->scratch_slots = partial > 0 ? (P + 2 * plan->segments) * groups : 0;
   return KVRA_OK;
 }
 
-int64_t attn_static_scratch_bytes() { return static_cast<int64_t>(sizeof(scratch)); }
+int64_t attn_static_scratch_bytes() { return static_cast<int64_t>(kStaticSlots) * kPartialFloats(128) * sizeof(float); }
 
 #ifdef KVRA_TRACE
 namespace {
@@ -779,55 +987,143 @@ long long g_trace_groups = 0;
 }  // namespace
 #endif
 
+namespace {
+
+// The shape and schedule fields of the kernel arguments.
+void schedule_args(const AttnPlan& plan, int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_kv_heads,
+                   AttnArgs* a) {
+  a->prefix = static_cast<int>(prefix_len);
+  a->chunk = static_cast<int>(chunk_len);
+  a->H = n_q_heads;
+  a->Hkv = n_kv_heads;
+  a->G = n_q_heads / n_kv_heads;
+  a->nq_tiles = plan.row_tiles;
+  a->rows_per_wg = plan.rows_per_tile;
+  a->bn = plan.key_tile;
+  a->groups = plan.groups;
+  a->slots = plan.slots;
+  a->units = plan.units;
+  a->rounds = plan.rounds;
+  a->head_steps = plan.head_steps;
+  a->cut = plan.cut;
+  a->segments = plan.segments;
+  for (int c = 0; c <= plan.slots; ++c) {
+    a->fill_seg[c] = plan.fill_seg[c];
+    a->fill_off[c] = plan.fill_off[c];
+  }
+}
+
+}  // namespace
+
+int list_chunk_attn_pieces(int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_kv_heads, int head_dim,
+                           int cus, int32_t* records, int64_t capacity, int64_t* count_out) {
+  AttnPlan plan;
+  const int rc = plan_chunk_attn(prefix_len, chunk_len, n_q_heads, n_kv_heads, head_dim, cus, true, &plan);
+  if (rc != KVRA_OK) return rc;
+  AttnArgs a;
+  schedule_args(plan, prefix_len, chunk_len, n_q_heads, n_kv_heads, &a);
+  int64_t count = 0;
+  for (int wg = 0; wg < plan.groups * plan.slots; ++wg) {
+    const int x = wg % plan.groups, c = wg / plan.groups;
+    PieceWalker walker(a, x, c);
+    Piece pc;
+    while (walker.next(a, &pc)) {
+      if (count < capacity && records != nullptr) {
+        int listed = 0, found = 0;
+        if (pc.slot >= 0)
+          for_each_piece_of_segment(a, pc.seg, [&](int slot) { ++listed; found += slot == pc.slot; });
+        int32_t* r = records + count * kPieceRecordInts;
+        r[0] = wg;
+        r[1] = pc.g;
+        r[2] = pc.qt;
+        r[3] = pc.jt0;
+        r[4] = pc.jt1;
+        r[5] = pc.n;
+        r[6] = pc.slot >= 0 ? x * slots_per_group(a) + pc.slot : -1;
+        r[7] = listed;
+        r[8] = found;
+        r[9] = pc.slot >= 0 ? x * kMaxSlots + pc.seg : -1;
+      }
+      ++count;
+    }
+  }
+  if (count_out != nullptr) *count_out = count;
+  return KVRA_OK;
+}
+
+namespace {
+
+// The schedules of the last few distinct shapes: a prefill loop calls with the same handful of
+// (prefix, chunk) pairs layer after layer, and working a schedule out takes tens of microseconds.
+struct PlanCacheEntry {
+  int64_t prefix_len, chunk_len;
+  int n_q_heads, n_kv_heads, head_dim, cus, scratch_available;
+  bool valid;
+  AttnPlan plan;
+};
+constexpr int kPlanCacheEntries = 32;
+PlanCacheEntry g_plan_cache[kPlanCacheEntries] = {};
+int g_plan_cache_next = 0;
+std::mutex g_plan_cache_mutex;
+
+int cached_plan(int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_kv_heads, int head_dim, int cus,
+                bool scratch_available, AttnPlan* plan) {
+  std::lock_guard<std::mutex> lock(g_plan_cache_mutex);
+  for (const PlanCacheEntry& e : g_plan_cache)
+    if (e.valid && e.prefix_len == prefix_len && e.chunk_len == chunk_len && e.n_q_heads == n_q_heads &&
+        e.n_kv_heads == n_kv_heads && e.head_dim == head_dim && e.cus == cus &&
+        e.scratch_available == static_cast<int>(scratch_available)) {
+      *plan = e.plan;
+      return KVRA_OK;
+    }
+  const int rc = plan_chunk_attn(prefix_len, chunk_len, n_q_heads, n_kv_heads, head_dim, cus, scratch_available, plan);
+  if (rc != KVRA_OK) return rc;
+  PlanCacheEntry& e = g_plan_cache[g_plan_cache_next];
+  g_plan_cache_next = (g_plan_cache_next + 1) % kPlanCacheEntries;
+  e = PlanCacheEntry{prefix_len, chunk_len, n_q_heads, n_kv_heads, head_dim, cus, static_cast<int>(scratch_available), true, *plan};
+  return KVRA_OK;
+}
+
+}  // namespace
+
 int launch_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
                       int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_kv_heads, int head_dim,
                       float scale, void* out, hipStream_t stream, bool static_scratch_only) {
   int cus = 0;
-  float* scratch_ptr = static_scratch_only ? static_scratch(&cus) : device_scratch(stream, &cus);
+  int64_t slots_owned = kStaticSlots;
+  float* scratch_ptr = static_scratch_only ? static_scratch(&cus) : device_scratch(stream, &cus, &slots_owned);
   if (static_scratch_only && scratch_ptr == nullptr) return KVRA_ENODEVICE;
   AttnPlan plan;
-  const int rc0 = plan_chunk_attn(prefix_len, chunk_len, n_q_heads, n_kv_heads, head_dim, cus, scratch_ptr != nullptr, &plan);
+  const int rc0 = cached_plan(prefix_len, chunk_len, n_q_heads, n_kv_heads, head_dim, cus, scratch_ptr != nullptr, &plan);
   if (rc0 != KVRA_OK) return rc0;
-  if (static_scratch_only &&
-      attn_partial_bytes(head_dim) * plan.split_units * plan.segments > attn_static_scratch_bytes())
-    return KVRA_ESCRATCH;
+  if (plan.scratch_slots > slots_owned) return KVRA_ESCRATCH;   // only the fixed array can be too small
   AttnArgs a;
+  schedule_args(plan, prefix_len, chunk_len, n_q_heads, n_kv_heads, &a);
   a.q = static_cast<const __bf16*>(q);
   a.k = static_cast<const __bf16*>(k_cache);
   a.v = static_cast<const __bf16*>(v_cache);
   a.out = static_cast<__bf16*>(out);
-  a.prefix = static_cast<int>(prefix_len);
-  a.chunk = static_cast<int>(chunk_len);
-  a.H = n_q_heads;
-  a.Hkv = n_kv_heads;
-  a.G = n_q_heads / n_kv_heads;
-  a.nq_tiles = plan.row_tiles;
-  a.rows_per_wg = plan.rows_per_tile;
   a.c_log2 = scale * 1.4426950408889634f;
-  a.bn = plan.key_tile;
-  a.scratch = plan.segments > 1 ? scratch_ptr : nullptr;
-  a.n_whole = plan.whole_units;
-  a.n_split = plan.split_units;
-  a.segments = plan.segments;
+  a.scratch = plan.partial_pieces > 0 ? scratch_ptr : nullptr;
+  a.counters = scratch_ptr != nullptr
+      ? reinterpret_cast<int*>(scratch_ptr + static_cast<size_t>(slots_owned) * kPartialFloats(128)) : nullptr;
+  const int workgroups = plan.groups * plan.slots;
 #ifdef KVRA_TRACE
-  a.trace = (a.n_whole + static_cast<long long>(a.n_split) * a.segments <= g_trace_groups) ? g_trace_buf : nullptr;
+  a.trace = workgroups <= g_trace_groups ? g_trace_buf : nullptr;
 #endif
   const unsigned smem = 2u * kStages * static_cast<unsigned>(a.bn) * static_cast<unsigned>(head_dim) * 2u;   // K ring + V ring
   const dim3 b3(kThreads);
-  const dim3 g_main(static_cast<unsigned>(a.n_whole + static_cast<int64_t>(a.n_split) * a.segments));
-  const int rc = head_dim == 128 ? launch_kernel(chunk_attn_kernel<128>, g_main, b3, a, stream, smem)
-                                 : launch_kernel(chunk_attn_kernel<64>, g_main, b3, a, stream, smem);
-  if (rc != KVRA_OK || a.segments == 1) return rc;
-  const dim3 g_fix(static_cast<unsigned>(a.n_split * kWaves * (head_dim / 32)));
-  return head_dim == 128 ? launch_kernel(chunk_attn_fixup_kernel<128>, g_fix, dim3(64), a, stream)
-                         : launch_kernel(chunk_attn_fixup_kernel<64>, g_fix, dim3(64), a, stream);
+  const dim3 g_main(static_cast<unsigned>(workgroups));
+  return head_dim == 128 ? launch_kernel(chunk_attn_kernel<128>, g_main, b3, a, stream, smem)
+                         : launch_kernel(chunk_attn_kernel<64>, g_main, b3, a, stream, smem);
 }
 
 }  // namespace kvra
 
 #ifdef KVRA_TRACE
-// Timeline build only: the device buffer (8 words of 8 bytes per workgroup) that the next kvra_chunk_attn
-// launches stamp; a launch with more workgroups than `workgroups` leaves no stamps.  NULL detaches.
+// Timeline build only: the device buffer (8 words of 8 bytes per piece) that the next kvra_chunk_attn
+// launches stamp (8 pieces per workgroup); a launch with more workgroups than `workgroups` leaves no stamps.
+// NULL detaches.
 extern "C" int kvra_trace_attach(void* device_buffer, long long workgroups) {
   kvra::g_trace_buf = static_cast<unsigned long long*>(device_buffer);
   kvra::g_trace_groups = device_buffer != nullptr ? workgroups : 0;

@@ -21,17 +21,48 @@ int launch_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
 int64_t attn_static_scratch_bytes();   // size of the fixed scratch array kvra_chunk_attn_noalloc uses
 
 // Launch shape of kvra_chunk_attn for a device with `cus` compute units (pure host arithmetic).
+//
+// Units.  A unit is one kv head x one tile of rows_per_tile query rows walked over the key tiles it can
+// see (`steps` of them).  The kv heads are dealt to `groups` groups (8 = one per XCD when the head count
+// and the CU count allow, else 1); every group has the same list of units, longest first, and `slots`
+// persistent workgroups, one per CU.
+//
+// Schedule of a slot.  Round 0: slot c runs unit c - only its first head_steps key tiles if it is one of
+// the `cut` longest units (cutting is considered while there are fewer than two complete rounds).  Rounds
+// 1 .. rounds-1: whole units (round k, slot c: unit k * slots + c, every second round in reverse slot order
+// so that long and short units add up alike).  What is left over - the tails of the cut units, then the
+// units beyond the complete rounds - forms `segments` key ranges laid end to end; slot c takes the part of
+// that line from (fill_seg[c], fill_off[c]) to (fill_seg[c+1], fill_off[c+1]), chosen so that all slots
+// finish together.  A piece that is not a whole unit leaves its un-normalised result in the scratch; the
+// piece of a unit that finishes last merges them.
+constexpr int kMaxSlots = 256;
 struct AttnPlan {
   int row_tiles;       // row tiles per kv head
   int rows_per_tile;   // virtual rows (token * group + head in group) per workgroup, <= 256
   int key_tile;        // keys per tile step
-  int whole_units;     // (kv head, row tile) units that run as one workgroup
-  int split_units;     // units cut into `segments` key segments, one workgroup each, merged by the fix-up kernel
-  int segments;        // 1 = no key-split
+  int groups;
+  int slots;           // per group, <= kMaxSlots
+  int units;           // per group
+  int rounds;
+  int head_steps;      // 0 = no unit is cut
+  int cut;             // units 0 .. cut-1 of the first round stop after head_steps key tiles
+  int segments;
+  int steps_per_slot;  // planned tile steps (plus the per-piece allowance) of the busiest slot
+  int partial_pieces;  // pieces (all groups) that go through the scratch
+  int scratch_slots;   // partial-result slots the launch may touch (all groups)
+  unsigned fill_seg[kMaxSlots + 1];
+  unsigned fill_off[kMaxSlots + 1];
 };
-int64_t attn_partial_bytes(int head_dim);   // scratch bytes per (split unit, key segment)
+int64_t attn_partial_bytes(int head_dim);   // scratch bytes per partial-result slot
+int64_t attn_counter_bytes();               // scratch bytes of the merge counters, behind the slots
 int plan_chunk_attn(int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_kv_heads, int head_dim,
                     int cus, bool scratch_available, AttnPlan* plan);
+// Every piece of the launch as kPieceRecordInts ints: workgroup, kv head, row tile, first key tile, end key
+// tile, key tiles of the unit, partial-result slot (-1: whole unit), pieces the merge of its unit reads,
+// whether its own slot is among them, merge counter (-1: none).
+constexpr int kPieceRecordInts = 10;
+int list_chunk_attn_pieces(int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_kv_heads, int head_dim,
+                           int cus, int32_t* records, int64_t capacity, int64_t* count_out);
 
 // out[m, n_out] = x[m, k] . w[n_out, k]^T (+ residual), or silu(x . w^T) * (x . w2^T) when w2 is given.
 // The n_out output columns are split over n_seg (1..3) dense matrices of seg_cols[s] columns each.

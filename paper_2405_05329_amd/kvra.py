@@ -33,7 +33,10 @@ class KvraError(RuntimeError):
 class KvraAttnPlan(ctypes.Structure):
     """Mirror of `kvra_attn_plan` in include/kvra.h."""
     _fields_ = [("row_tiles", ctypes.c_int), ("rows_per_tile", ctypes.c_int), ("key_tile", ctypes.c_int),
-                ("whole_units", ctypes.c_int), ("split_units", ctypes.c_int), ("segments", ctypes.c_int),
+                ("groups", ctypes.c_int), ("slots", ctypes.c_int), ("units", ctypes.c_int),
+                ("rounds", ctypes.c_int), ("head_steps", ctypes.c_int), ("cut_units", ctypes.c_int),
+                ("segments", ctypes.c_int),
+                ("steps_per_slot", ctypes.c_int), ("partial_pieces", ctypes.c_int),
                 ("scratch_bytes", ctypes.c_int64)]
 
 
@@ -62,6 +65,9 @@ def _load() -> ctypes.CDLL:
     lib.kvra_chunk_attn_noalloc_scratch_bytes.argtypes = []
     lib.kvra_chunk_attn_plan.restype = i32
     lib.kvra_chunk_attn_plan.argtypes = [i64, i64, i32, i32, i32, i32, ctypes.POINTER(KvraAttnPlan)]
+    lib.kvra_chunk_attn_pieces.restype = i32
+    lib.kvra_chunk_attn_pieces.argtypes = [i64, i64, i32, i32, i32, i32, ctypes.POINTER(ctypes.c_int32), i64,
+                                           ctypes.POINTER(i64)]
     lib.kvra_balance.restype = i32
     lib.kvra_balance.argtypes = [i64, i32, i64, ctypes.c_void_p, vp, ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)]
     lib.kvra_equal_split.restype = i32
@@ -186,6 +192,26 @@ def kvra_chunk_attn_plan(prefix_len, chunk_len, n_q_heads, n_kv_heads, head_dim,
     if rc != 0:
         raise KvraError(rc, "kvra_chunk_attn_plan")
     return {name: getattr(plan, name) for name, _ in KvraAttnPlan._fields_}
+
+
+PIECE_FIELDS = ("workgroup", "kv_head", "row_tile", "jt0", "jt1", "unit_steps", "slot", "merge_pieces",
+                "in_merge_list", "counter")
+
+
+def kvra_chunk_attn_pieces(prefix_len, chunk_len, n_q_heads, n_kv_heads, head_dim, n_cus) -> list:
+    """The pieces of the launch plan as a list of dicts with the keys PIECE_FIELDS."""
+    count = ctypes.c_int64()
+    rc = _lib.kvra_chunk_attn_pieces(prefix_len, chunk_len, n_q_heads, n_kv_heads, head_dim, n_cus, None, 0,
+                                     ctypes.byref(count))
+    if rc != 0:
+        raise KvraError(rc, "kvra_chunk_attn_pieces")
+    n = count.value
+    buf = (ctypes.c_int32 * (10 * max(n, 1)))()
+    rc = _lib.kvra_chunk_attn_pieces(prefix_len, chunk_len, n_q_heads, n_kv_heads, head_dim, n_cus, buf, n,
+                                     ctypes.byref(count))
+    if rc != 0:
+        raise KvraError(rc, "kvra_chunk_attn_pieces")
+    return [dict(zip(PIECE_FIELDS, buf[10 * i:10 * i + 10])) for i in range(n)]
 
 
 def kvra_balance(context_len, n_chunks, granularity, cost=None):

@@ -1,8 +1,8 @@
 """Where the time of each kvra_chunk_attn launch of a workload goes, from per-workgroup time stamps.
 
 Needs the timeline build of the library (python -m paper_2405_05329_amd.build --trace), whose attention
-kernel stamps the constant 100 MHz clock at workgroup entry, first tile step, last tile step done and
-exit, together with the compute unit it ran on.  For every chunk of the workload this prints one table row:
+kernel stamps the constant 100 MHz clock at the start of every piece of work, its first tile step, its last
+tile step done and its end, together with the compute unit it ran on.  For every chunk of the workload this prints one table row:
 
   launch     HIP-event time of the call (median of --reps, product library, no stamps)
   span       first workgroup entry to last workgroup exit (timeline build)
@@ -10,12 +10,13 @@ exit, together with the compute unit it ran on.  For every chunk of the workload
              workgroups of the chunk that fills the chip best, printed below the table)
   steps      time the CUs spent inside tile loops, averaged over CUs; beyond `ideal` this is partly filled
              row tiles and the slower or faster clock of that launch
-  pro/epi    time between entry and first step, and between last step and exit, per CU
-  gap        time a CU sat between two workgroups, per CU
+  pro/epi    time between a piece's start and its first step, and between its last step and its end (the
+             merge of a cut unit is part of the last piece's epi), per CU
+  gap        time a CU sat between two pieces, per CU
   ramp       first entry on a CU after the first entry anywhere, averaged over CUs
   tail       last exit anywhere minus the last exit on a CU, averaged over CUs (idle CUs at the end:
              partly filled last round, uneven units)
-  launch - span   dispatch of the kernel, and for a key-split launch the merge kernel that follows it
+  launch - span   dispatch of the kernel
 
 Per CU, span = ramp + pro + steps + epi + gap + tail; the columns are these terms averaged over the CUs
 (a CU that never got a workgroup counts as ramp = span).
@@ -36,6 +37,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 TRACE_WORDS = 8
+TRACE_PIECES = 8   # pieces per workgroup that leave stamps
 TICK_US = 0.01   # 100 MHz
 
 
@@ -44,13 +46,14 @@ def main():
     ap.add_argument("--workload", default="llama7b_16k_balanced")
     ap.add_argument("--reps", type=int, default=20)
     ap.add_argument("--dump", default=None, help="write the raw stamps of every chunk to this .npz")
+    ap.add_argument("--trace-lib", default=None, help="timeline build to load (default: libkvra_trace.so beside this file)")
     args = ap.parse_args()
 
     import torch
     from paper_2405_05329_amd import kvra, synth
 
     pkg = os.path.dirname(os.path.abspath(__file__))
-    tlib = ctypes.CDLL(os.path.join(pkg, "libkvra_trace.so"))
+    tlib = ctypes.CDLL(args.trace_lib or os.path.join(pkg, "libkvra_trace.so"))
     i64, i32, f32, vp = ctypes.c_int64, ctypes.c_int, ctypes.c_float, ctypes.c_void_p
     tlib.kvra_chunk_attn.restype = i32
     tlib.kvra_chunk_attn.argtypes = [vp, vp, vp, i64, i64, i32, i32, i32, f32, vp, vp]
@@ -72,8 +75,8 @@ def main():
     v_cache = torch.zeros_like(k_cache)
     out = torch.empty((C, H, d), dtype=torch.bfloat16, device="cuda")
     kvra.kvra_append_kv(k_in, v_in, q, k_cache, v_cache, 0, C, C, H, Hkv, d, synth.ROPE_BASE)
-    max_groups = 1 << 16
-    trace = torch.zeros((max_groups, TRACE_WORDS), dtype=torch.int64, device="cuda")
+    max_groups = 1 << 12
+    trace = torch.zeros((max_groups * TRACE_PIECES, TRACE_WORDS), dtype=torch.int64, device="cuda")
     torch.cuda.synchronize()
 
     rows, dumps = [], {}
@@ -101,8 +104,9 @@ def main():
                                       scale, out[lo:lo + c].data_ptr(), None)
             assert rc == 0, rc
             torch.cuda.synchronize()
-            n_groups = plan["whole_units"] + plan["split_units"] * plan["segments"]
-            t = trace[:n_groups].cpu().numpy().astype(np.uint64)
+            n_groups = plan["groups"] * plan["slots"]
+            t = trace[:n_groups * TRACE_PIECES].cpu().numpy().astype(np.uint64)
+            t = t[t[:, 3] != 0]                       # one record per piece a workgroup ran
             spans.append((int(t[:, 3].max() - t[:, 0].min()), t))
         tlib.kvra_trace_attach(None, 0)
         spans.sort(key=lambda x: x[0])
@@ -142,11 +146,11 @@ def main():
     print(f"steady step time {t_step:.3f} us = median time per tile step ({best['plan']['key_tile']} keys x "
           f"{best['plan']['rows_per_tile']} rows) of the workgroups of chunk {best['chunk']} ({best['groups']} workgroups)")
     print()
-    print("| chunk | prefix | c | units x segments | row tile | launch | TFLOP/s | span | ideal | steps | pro | epi | gap | ramp | tail | launch - span | step med |")
+    print("| chunk | prefix | c | units, pieces | row tile | launch | TFLOP/s | span | ideal | steps | pro | epi | gap | ramp | tail | launch - span | step med |")
     print("|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|")
     for r in rows:
         p = r["plan"]
-        shape = f"{p['whole_units']}" + (f" + {p['split_units']} x {p['segments']}" if p["segments"] > 1 else "")
+        shape = f"{p['units'] * p['groups']} u, {r['groups']} p" + (f", {p['partial_pieces']} merged" if p["partial_pieces"] else "")
         ideal = r["total_steps"] / cus * t_step
         print(f"| {r['chunk']} | {r['prefix']} | {r['c']} | {shape} | {p['rows_per_tile']} | {r['launch']:.1f} | "
               f"{flops(r['prefix'], r['c']) / r['launch'] / 1e6:.0f} | {r['span']:.1f} | {ideal:.1f} | {r['in_steps']:.1f} | "

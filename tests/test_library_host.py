@@ -288,60 +288,109 @@ def test_layer_and_linear_reject_bad_arguments_before_any_launch():
 
 
 # ------------------------------------------------------------------ launch plan of kvra_chunk_attn
-def test_attention_launch_plan_of_the_16k_workload():
-    """Llama-7B shape, 8 balanced chunks, 256 compute units: which chunks run whole and which have
-    the units of their last round of CUs cut into key segments."""
+PIECE_ALLOWANCE = 5     # tile steps the plan charges per piece for starting and finishing it
+
+
+def _unit_steps(prefix, c, G, rows_per_tile, key_tile, qt):
+    row_hi = min((qt + 1) * rows_per_tile, c * G)
+    return (prefix + (row_hi - 1) // G) // key_tile + 1
+
+
+def _check_schedule(prefix, c, H, Hkv, d, cus):
+    """Every (kv head, row tile) unit is covered exactly once by the pieces of the plan; partial pieces of a
+    unit share one counter, have distinct scratch slots inside the declared scratch, and are exactly the
+    pieces its merge reads; no workgroup beyond groups * slots; piece lengths respect the minimum."""
+    p = kvra.kvra_chunk_attn_plan(prefix, c, H, Hkv, d, cus)
+    pieces = kvra.kvra_chunk_attn_pieces(prefix, c, H, Hkv, d, cus)
+    G = H // Hkv
+    rows = c * G
+    assert p["rows_per_tile"] % 32 == 0 and 32 <= p["rows_per_tile"] <= 256
+    assert p["row_tiles"] * p["rows_per_tile"] >= rows > (p["row_tiles"] - 1) * p["rows_per_tile"]
+    assert p["key_tile"] == (128 if d == 64 else 64)
+    assert p["groups"] in (1, 8) and p["groups"] * p["slots"] <= max(cus, 1) and p["slots"] <= 256
+    assert p["units"] * p["groups"] == p["row_tiles"] * Hkv
+    covered = {}
+    slots, per_wg = set(), {}
+    partial = 0
+    for pc in pieces:
+        assert 0 <= pc["workgroup"] < p["groups"] * p["slots"]
+        n = _unit_steps(prefix, c, G, p["rows_per_tile"], p["key_tile"], pc["row_tile"])
+        assert pc["unit_steps"] == n and 0 <= pc["jt0"] < pc["jt1"] <= n
+        covered.setdefault((pc["kv_head"], pc["row_tile"]), []).append(pc)
+        per_wg[pc["workgroup"]] = per_wg.get(pc["workgroup"], 0) + (pc["jt1"] - pc["jt0"]) + PIECE_ALLOWANCE
+        whole = pc["jt0"] == 0 and pc["jt1"] == n
+        assert whole == (pc["slot"] < 0) == (pc["counter"] < 0)
+        if not whole:
+            partial += 1
+            assert pc["slot"] not in slots and 0 <= pc["slot"] * 8 * (4 * 16 + 2) * 64 * 4 < p["scratch_bytes"]
+            slots.add(pc["slot"])
+            assert pc["in_merge_list"] == 1 and 0 <= pc["counter"] < 8 * 256
+    assert partial == p["partial_pieces"]
+    assert (partial == 0) == (p["scratch_bytes"] == 0)
+    assert len(covered) == p["row_tiles"] * Hkv
+    counters = set()
+    for (g, qt), pcs in covered.items():
+        pcs.sort(key=lambda r: r["jt0"])
+        assert pcs[0]["jt0"] == 0 and pcs[-1]["jt1"] == pcs[0]["unit_steps"]
+        assert all(a["jt1"] == b["jt0"] for a, b in zip(pcs[:-1], pcs[1:]))
+        if len(pcs) > 1:
+            assert all(r["merge_pieces"] == len(pcs) for r in pcs)
+            assert len({r["counter"] for r in pcs}) == 1 and pcs[0]["counter"] not in counters
+            counters.add(pcs[0]["counter"])
+            assert min(r["jt1"] - r["jt0"] for r in pcs) >= 8
+    assert max(per_wg.values()) <= p["steps_per_slot"] + 8
+    return p, pieces, per_wg
+
+
+def test_attention_schedule_of_the_16k_workload():
+    """Llama-7B shape, 8 balanced chunks, 256 compute units: 8 groups of 32 slots, and every slot's load (tile
+    steps plus five per piece) within a few steps of the ideal share of its group."""
     H, d, cus = 32, 128, 256
-    want = {  # (prefix, chunk): (row tiles, rows per tile, whole units, split units, segments)
-        (0, 5824): (23, 256, 736, 0, 1),          # 224 units in the last round: no S gets it below 0.7
-        (5824, 2368): (10, 256, 256, 64, 3),      # 320 units: one full round, 64 units in thirds
-        (8192, 1856): (8, 256, 256, 0, 1),        # exactly one round
-        (10048, 1536): (6, 256, 192, 0, 1),       # 192 units: quarter pieces would need 3 rounds (0.75)
-        (11584, 1344): (6, 224, 192, 0, 1),
-        (12928, 1280): (5, 256, 0, 160, 3),       # 160 units in thirds: 480 pieces, two rounds (0.67)
-        (14208, 1088): (5, 224, 0, 160, 3),
-        (15296, 1088): (5, 224, 0, 160, 3),
-    }
-    for (prefix, c), (tiles, rows, whole, split, seg) in want.items():
-        p = kvra.kvra_chunk_attn_plan(prefix, c, H, H, d, cus)
-        assert (p["row_tiles"], p["rows_per_tile"], p["whole_units"], p["split_units"], p["segments"]) == \
-            (tiles, rows, whole, split, seg), (prefix, c, p)
-        assert p["key_tile"] == 64
+    bounds = [0, 5824, 8192, 10048, 11584, 12928, 14208, 15296, 16384]
+    want = {0: (23, 256, 92, 2, 0), 1: (10, 256, 40, 1, 0), 2: (8, 256, 32, 1, 8), 3: (6, 256, 24, 0, 24),
+            4: (6, 224, 24, 0, 24), 5: (5, 256, 20, 0, 20), 6: (5, 224, 20, 0, 20), 7: (5, 224, 20, 0, 20)}
+    for i, (tiles, rows, units, rounds, cut) in want.items():
+        prefix, c = bounds[i], bounds[i + 1] - bounds[i]
+        p, pieces, per_wg = _check_schedule(prefix, c, H, H, d, cus)
+        assert (p["row_tiles"], p["rows_per_tile"], p["units"], p["rounds"], p["cut_units"]) == (tiles, rows, units, rounds, cut)
+        assert (p["groups"], p["slots"]) == (8, 32)
+        total = sum(pc["jt1"] - pc["jt0"] for pc in pieces)
+        ideal = total / 256
+        assert len(per_wg) == 256                                   # no idle compute unit
+        assert max(per_wg.values()) <= 1.08 * ideal + 3 * PIECE_ALLOWANCE   # allowances included
+        assert sorted(per_wg.values())[8] >= 0.9 * ideal               # (the last slot of a group takes what is left)
 
 
-def test_attention_launch_plan_invariants_and_decode_like_shapes():
-    # a few tokens behind a long prefix: one unit per head, cut as finely as the round allows
-    p = kvra.kvra_chunk_attn_plan(20000, 8, 32, 32, 128, 256)
-    assert (p["row_tiles"], p["rows_per_tile"], p["whole_units"], p["split_units"], p["segments"]) == (1, 32, 0, 32, 8)
-    # too few keys for 16 key tiles per piece: whole
-    p = kvra.kvra_chunk_attn_plan(100, 8, 32, 32, 128, 256)
-    assert (p["split_units"], p["segments"], p["scratch_bytes"]) == (0, 1, 0)
-    # grouped queries fold into the row index; head_dim 64 walks 128-key tiles
-    p = kvra.kvra_chunk_attn_plan(0, 4096, 71, 1, 64, 256)
-    assert p["key_tile"] == 128 and p["row_tiles"] == (4096 * 71 + 255) // 256
+def test_attention_schedule_invariants_on_random_shapes():
     rng = random.Random(5)
-    for _ in range(300):
-        H, Hkv, d = rng.choice([(32, 32, 128), (32, 8, 128), (32, 1, 128), (71, 1, 64), (16, 16, 64)])
-        prefix, c = rng.choice([0, 1, 63, 4096, 30000]), rng.choice([1, 7, 64, 300, 1088, 5000])
-        cus = rng.choice([8, 64, 256, 304])
-        p = kvra.kvra_chunk_attn_plan(prefix, c, H, Hkv, d, cus)
-        rows = c * (H // Hkv)
-        assert p["rows_per_tile"] % 32 == 0 and 32 <= p["rows_per_tile"] <= 256
-        assert p["row_tiles"] * p["rows_per_tile"] >= rows > (p["row_tiles"] - 1) * p["rows_per_tile"]
-        assert p["whole_units"] + p["split_units"] == p["row_tiles"] * Hkv
-        assert (p["segments"] == 1) == (p["split_units"] == 0)
-        assert p["whole_units"] % cus == 0 or p["split_units"] == 0
-        assert p["split_units"] * p["segments"] <= 3 * cus                  # scratch slots
-        assert p["scratch_bytes"] == (p["split_units"] * p["segments"] * 8 * (d // 32 * 16 + 2) * 64 * 4
-                                      if p["split_units"] else 0)
-        if p["segments"] > 1:                                               # at least 16 key tiles per piece
-            last_rows = min(p["rows_per_tile"], rows)
-            assert ((prefix + (last_rows - 1) // (H // Hkv)) // p["key_tile"] + 1) // p["segments"] >= 16
+    for _ in range(250):
+        H, Hkv, d = rng.choice([(32, 32, 128), (32, 8, 128), (32, 1, 128), (71, 1, 64), (16, 16, 64), (6, 3, 128)])
+        prefix = rng.choice([0, 1, 63, 500, 4096, 30000])
+        c = rng.choice([1, 7, 64, 300, 1088, 2500])
+        cus = rng.choice([1, 8, 64, 256, 304])
+        _check_schedule(prefix, c, H, Hkv, d, cus)
+
+
+def test_attention_schedule_of_decode_like_and_short_shapes():
+    # a few tokens behind a long prefix: one unit per head, cut so that every compute unit gets a piece
+    p, pieces, per_wg = _check_schedule(20000, 8, 32, 32, 128, 256)
+    assert (p["row_tiles"], p["rows_per_tile"], p["units"], p["rounds"], p["cut_units"]) == (1, 32, 4, 0, 4)
+    assert len(per_wg) == 256 and max(per_wg.values()) <= 313 * 32 / 256 + 3 * PIECE_ALLOWANCE + 8
+    # too few key tiles to cut anything: whole units
+    p, pieces, _ = _check_schedule(100, 8, 32, 32, 128, 256)
+    assert p["partial_pieces"] == 0 and p["scratch_bytes"] == 0 and len(pieces) == 32
+    # the first chunk of the 4k context in four equal chunks: 128 units on 256 compute units
+    p, pieces, per_wg = _check_schedule(0, 1024, 32, 32, 128, 256)
+    assert p["units"] == 16 and p["cut_units"] == 4 and max(per_wg.values()) < 16 + PIECE_ALLOWANCE   # 16: the longest unit whole
+    # grouped queries fold into the row index; head_dim 64 walks 128-key tiles; one group when the kv heads
+    # cannot be dealt to eight
+    p, pieces, _ = _check_schedule(0, 4096, 71, 1, 64, 256)
+    assert p["key_tile"] == 128 and p["row_tiles"] == (4096 * 71 + 255) // 256 and (p["groups"], p["slots"]) == (1, 256)
 
 
 def test_noalloc_scratch_holds_every_plan_of_a_256_cu_device_and_not_every_plan_of_a_larger_one():
     """kvra_chunk_attn_noalloc refuses (KVRA_ESCRATCH) a launch whose plan needs more partial-result
-    bytes than its fixed array holds.  That array is sized for three slots per CU of a 256-CU device:
+    slots than its fixed array holds.  That array is sized for three slots per CU of a 256-CU device:
     no plan for 256 CUs exceeds it, while a hypothetical 512-CU device has plans that do."""
     cap = kvra.kvra_chunk_attn_noalloc_scratch_bytes()
     assert cap == 768 * 8 * (4 * 16 + 2) * 64 * 4
@@ -437,7 +486,7 @@ def test_header_is_plain_c_and_a_c_program_can_call_the_host_entry_points(tmp_pa
         "  if (kvra_balance(16384, 8, 64, NULL, NULL, b, &m) != KVRA_OK) return 1;\n"
         "  if (kvra_chunk_attn_plan(b[7], b[8] - b[7], 32, 32, 128, 256, &plan) != KVRA_OK) return 2;\n"
         '  for (int k = 0; k < 9; ++k) printf("%lld ", (long long)b[k]);\n'
-        '  printf("| %d %d %d %s\\n", plan.whole_units, plan.split_units, plan.segments, kvra_strerror(KVRA_ERANGE));\n'
+        '  printf("| %d %d %d %s\\n", plan.slots, plan.head_steps, plan.segments, kvra_strerror(KVRA_ERANGE));\n'
         "  return 0;\n}\n")
     exe = tmp_path / "host"
     lib_dir = os.path.dirname(kvra.LIB_PATH)
@@ -448,4 +497,4 @@ def test_header_is_plain_c_and_a_c_program_can_call_the_host_entry_points(tmp_pa
     want_b = kvra.kvra_balance(16384, 8, 64)[0]
     assert [int(x) for x in bounds.split()] == want_b
     plan = kvra.kvra_chunk_attn_plan(want_b[7], want_b[8] - want_b[7], 32, 32, 128, 256)
-    assert [int(x) for x in rest.split()[:3]] == [plan["whole_units"], plan["split_units"], plan["segments"]]
+    assert [int(x) for x in rest.split()[:3]] == [plan["slots"], plan["head_steps"], plan["segments"]]

@@ -12,7 +12,7 @@ pytestmark = pytest.mark.gpu
 
 MAX_ABS, MEAN_ABS = 2e-2, 2e-3
 
-# (H, Hkv, d, prefix, c): key-split launches (few long units), large then small, then one that is not split
+# (H, Hkv, d, prefix, c): launches whose units are cut (few long units), large then small, then one that is not
 SEQUENCE = [(32, 8, 128, 6000, 700), (32, 32, 128, 9000, 8), (8, 8, 64, 5000, 1), (4, 4, 128, 0, 300)]
 
 
@@ -40,7 +40,7 @@ def test_noalloc_equals_the_allocating_entry_point_two_calls_in_a_row():
         H, Hkv, d, prefix, c = p["case"]
         plan = kvra.kvra_chunk_attn_plan(prefix, c, H, Hkv, d, cus)
         assert plan["scratch_bytes"] <= kvra.kvra_chunk_attn_noalloc_scratch_bytes()
-        split.append(plan["segments"] > 1)
+        split.append(plan["partial_pieces"] > 0)
     assert split[:3] == [True, True, True] and not split[3], split   # the first three go through the scratch
     torch.cuda.synchronize()
 
