@@ -440,6 +440,11 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, int* last
 #pragma unroll
       for (int e = 0; e < 8; ++e) pf[mb][si][e] = static_cast<__bf16>(0.0f);
 
+  // steps whose staging needs no bookkeeping (see the VALU block): K tile st + 2 and V tile st + 1 both exist
+  // and neither straddles the end of the cache
+  const int bulk_lo = 1 - phase;
+  const int bulk_hi = min(nt - 2, kt_ragged >= 0 ? kt_ragged - 2 : nt) - phase;
+
   // One tile step; RS = j % kStages is a compile-time value so that every LDS operand address is
   // a loop-invariant per-lane register plus an immediate.
   auto tile_step = [&](const int j, auto rs_tag) {
@@ -502,10 +507,19 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, int* last
     // The 2 LOADS loads are handed out one at a time and spread over the softmax below.  A tile
     // beyond the fragment is "loaded" with no lane enabled: no branch, so the loads can sit in
     // straight-line code.  The ragged last tile of the cache takes the clamped offsets.
-    const bool k_on = st >= 1 && st + 2 < nt, v_on = st >= 1 && st + 1 < nt;
+    // At head_dim 64, where this block is the longer of the two, only the steps near either end of the piece
+    // work any of this out: in the bulk of the steps, [bulk_lo, bulk_hi), both tiles exist and neither is
+    // the ragged one (a wave-uniform branch around scalar work: every scalar instruction of this block is
+    // issue time the matrix pipe waits for; measured +1.5 % at head_dim 64, -1 % at 128, where it stays out).
+    bool k_on = true, v_on = true, k_rag = false, v_rag = false;
+    if (D != 64 || j < bulk_lo || j >= bulk_hi) {
+      k_on = st >= 1 && st + 2 < nt;
+      v_on = st >= 1 && st + 1 < nt;
+      k_rag = st + 2 == kt_ragged;
+      v_rag = st + 1 == kt_ragged;
+    }
     const int issued = (k_on ? LOADS : 0) + (v_on ? LOADS : 0);
     const unsigned long long k_mask = __builtin_amdgcn_ballot_w64(k_on), v_mask = __builtin_amdgcn_ballot_w64(v_on);
-    const bool k_rag = st + 2 == kt_ragged, v_rag = st + 1 == kt_ragged;
     auto stage_piece = [&](int idx) __attribute__((always_inline)) {
       __builtin_amdgcn_sched_barrier(0);
       if (idx < LOADS)
