@@ -32,9 +32,12 @@ WORKLOAD = "llama7b_16k_balanced"
 # A measured constant, not a live reading: `source` names the tracked summary it was copied from and the
 # commit whose kernel that run profiled.
 ATTN_TRAFFIC = {
-    "llama7b_16k_balanced": {"bytes": 3.522e8,
-                             "source": "profiles/chunk_attn_append_llama7b_16k_balanced.md (key-split launches + merge kernel, "
-                                       "commit 899ef25; not yet re-measured for the persistent kernel)"},
+    "llama7b_16k_balanced": {"bytes": 4.900e8,
+                             "source": "profiles/chunk_attn_append_llama7b_16k_balanced.md: FETCH_SIZE 410.2 MiB + WRITE_SIZE "
+                                       "57.1 MiB per call (persistent kernel with the merge inside, commit ae5e3d2); above the "
+                                       "algorithmic bytes because row tiles of one head and the pieces of a cut unit read the "
+                                       "same K/V at different times (L2 hit rate 64 %); 2 TB/s at this launch time, a "
+                                       "quarter of the HBM peak, so not what bounds the kernel"},
 }
 
 
@@ -443,27 +446,73 @@ def main():
         table = {(pr, c): measure(pr, c) for pr in ps for c in cs if pr + c <= C and c >= 64}
         A = np.array([features(pr, c) for (pr, c) in table])
         y = np.array(list(table.values()))
-        coef, *_ = np.linalg.lstsq(A, y, rcond=None)
+        # the fit serves a search whose answer has every chunk near (step time / p): points near that time
+        # weigh most, tiny and huge launches little
+        t_star = ms_per_step / p
+        wt = np.exp(-((y - t_star) / (0.5 * t_star)) ** 2) + 0.02
+        coef, *_ = np.linalg.lstsq(A * wt[:, None], y * wt, rcond=None)
         resid = np.abs(A @ coef - y) / y
+        near = np.abs(y - t_star) <= 0.5 * t_star
+
+        feat_cache = {}
+
+        def model(prefix, c):
+            f = feat_cache.get((prefix, c))
+            if f is None:
+                f = feat_cache[(prefix, c)] = np.array(features(prefix, c))
+            return float(np.dot(coef, f))
+
+        # The fit is smooth where the kernel's time is not (the row-tile size and the cut of the schedule change
+        # with the shape), so the search is refined on measurements of its own candidates, as the paper's
+        # search is: every candidate partition is run, the ratio measured / model of each of its chunks is kept,
+        # and the cost near a measured point is the model times that ratio (Gaussian weights, widths C/16 in
+        # the prefix and C/64 in the chunk length; far from every measured point the model stands alone).
+        seen = []            # (prefix, chunk, measured / model)
+        w_prefix, w_chunk = C / 16.0, C / 64.0
 
         def cost(prefix, c):
-            return float(np.dot(coef, features(prefix, c)))
+            t = model(prefix, c)
+            if seen:
+                pts = np.array(seen)
+                w = np.exp(-(((pts[:, 0] - prefix) / w_prefix) ** 2 + ((pts[:, 1] - c) / w_chunk) ** 2))
+                s = float(w.sum())
+                if s > 1e-6:
+                    t *= 1.0 + float(np.dot(w, pts[:, 2] - 1.0)) / max(s, 1.0)
+            return t
 
-        t0 = time.perf_counter()
-        bal, mk = kvra.kvra_balance(C, p, 64, cost)
-        host_ms = (time.perf_counter() - t0) * 1e3
+        history, best = [], None
+        host_ms = 0.0
+        for it in range(6):
+            t0 = time.perf_counter()
+            bal, mk = kvra.kvra_balance(C, p, 64, cost)
+            host_ms += (time.perf_counter() - t0) * 1e3
+            _, tot = measured_chunks(bal)
+            history.append({"boundaries": bal, "predicted_ms": round(mk, 4), "measured_ms": round(float(tot.max()), 4)})
+            if best is None or tot.max() < best[1]:
+                best = (bal, float(tot.max()))
+            for i in range(p):
+                seen.append((bal[i], bal[i + 1] - bal[i], float(tot[i]) / model(bal[i], bal[i + 1] - bal[i])))
+            if it >= 1 and abs(mk - tot.max()) <= 0.03 * tot.max():
+                break
+        bal = best[0]
+        # fresh measurements of the kept candidate and of the workload's own boundaries, after the search ended
         _, bal_total = measured_chunks(bal)
         _, ref_total = measured_chunks(bounds)
+        mk = max(cost(bal[i], bal[i + 1] - bal[i]) for i in range(p))
         result["makespan"]["kvra_balance"] = {
             "cost_model": "t = a0 + steps_per_slot * (a1 + a2 * rows_per_tile / 256) + a3 * chunk, fitted to "
-                          f"{len(table)} measured (prefix, chunk) points; steps_per_slot and rows_per_tile from kvra_chunk_attn_plan",
+                          f"{len(table)} measured (prefix, chunk) points (steps_per_slot and rows_per_tile from "
+                          "kvra_chunk_attn_plan), times the measured / model ratio of the candidates the search has "
+                          "already run (Gaussian weights around each measured chunk)",
             "coefficients_ms": [float(x) for x in coef],
             "fit_error_mean": float(resid.mean()), "fit_error_max": float(resid.max()),
+            "fit_error_max_near_step_time": float(resid[near].max()) if near.any() else None,
+            "search": history,
             "boundaries": bal, "predicted_ms": mk, "measured_ms": float(bal_total.max()),
             "prediction_error": float(abs(mk - bal_total.max()) / bal_total.max()),
+            "model_only_prediction_error": float(abs(history[0]["predicted_ms"] - history[0]["measured_ms"]) / history[0]["measured_ms"]),
             "host_ms": host_ms,
             "workload_boundaries_measured_ms": float(ref_total.max()),
-            "workload_chunks_predicted_ms": [round(cost(bounds[i], bounds[i + 1] - bounds[i]), 4) for i in range(p)],
             "workload_chunks_measured_ms": [round(float(x), 4) for x in ref_total],
             "searched_chunks_predicted_ms": [round(cost(bal[i], bal[i + 1] - bal[i]), 4) for i in range(p)],
             "searched_chunks_measured_ms": [round(float(x), 4) for x in bal_total],
