@@ -132,7 +132,7 @@ int64_t kvra_chunk_attn_noalloc_scratch_bytes(void);
  * longest units (units are cut while there are fewer than two complete rounds).  Rounds 1 .. rounds-1 are
  * whole units.  The rest - the tails of the cut units, then the units beyond the complete rounds - is
  * `segments` key ranges laid end to end and shared out among the slots so that all finish together after
- * about `steps_per_slot` tile steps (five of which per piece are the allowance for starting and finishing it).
+ * about `steps_per_slot` tile steps (eight of which per piece are the allowance for starting and finishing it).
  * `partial_pieces` pieces (over all groups) are not whole units: they leave their un-normalised results in
  * the scratch (`scratch_bytes` = the partial-result slots the launch may touch x 132 KiB), and the piece
  * of a unit that finishes last merges them inside the kernel.

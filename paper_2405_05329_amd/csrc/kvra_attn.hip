@@ -854,7 +854,7 @@ float* static_scratch(int* cus_out) {
 
 // ---- the schedule (host arithmetic) --------------------------------------------------------------
 #ifndef KVRA_ALLOWANCE
-#define KVRA_ALLOWANCE 5
+#define KVRA_ALLOWANCE 8
 #endif
 #ifndef KVRA_MINPIECE
 #define KVRA_MINPIECE 8
