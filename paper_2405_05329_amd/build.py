@@ -58,5 +58,20 @@ def build(verbose: bool = False, extra_flags=(), trace: bool = False) -> str:
     return lib
 
 
+PROBE_LIB = os.path.join(PKG, "libkvra_probe.so")
+
+
+def build_probe() -> str:
+    """libkvra_probe.so: the matrix-pipe yardstick probe.py runs (one kernel, not part of the product library)."""
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    cmd = [hipcc, "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wno-unused-command-line-argument", *DEVICE_FLAGS,
+           "-x", "hip", os.path.join(CSRC, "kvra_probe.hip"), "-o", PROBE_LIB]
+    subprocess.run(cmd, check=True)
+    return PROBE_LIB
+
+
 if __name__ == "__main__":
-    print(build(verbose="-v" in sys.argv, trace="--trace" in sys.argv))
+    if "--probe" in sys.argv:
+        print(build_probe())
+    else:
+        print(build(verbose="-v" in sys.argv, trace="--trace" in sys.argv))

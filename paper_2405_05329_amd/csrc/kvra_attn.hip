@@ -728,6 +728,9 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, int* last
 // of segments).
 template <int D>
 __global__ __launch_bounds__(kThreads, 1) void chunk_attn_kernel(AttnArgs a) {
+#ifdef KVRA_TRACE
+  const unsigned long long t_entry = wall_clock64();   // before the first read of the arguments
+#endif
   extern __shared__ u32x4 smem[];
   __shared__ int last_flag;
   const int x = blockIdx.x % a.groups, c = blockIdx.x / a.groups;
@@ -749,7 +752,9 @@ __global__ __launch_bounds__(kThreads, 1) void chunk_attn_kernel(AttnArgs a) {
       asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw));
       asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
       rec[4] = (static_cast<unsigned long long>(xcc) << 32) | hw;
-      rec[5] = static_cast<unsigned long long>(pc.jt1 - pc.jt0);
+      // tile steps; for the workgroup's first piece also the time from kernel entry to the piece's start
+      // (reading the arguments and the schedule tables), in clock ticks, in the upper half
+      rec[5] = static_cast<unsigned long long>(pc.jt1 - pc.jt0) | (ordinal == 1 ? (rec[0] - t_entry) << 32 : 0ull);
       rec[6] = (static_cast<unsigned long long>(static_cast<unsigned>(pc.g)) << 32) | static_cast<unsigned>(pc.qt);
       rec[7] = (static_cast<unsigned long long>(static_cast<unsigned>(pc.slot + 1)) << 32) | static_cast<unsigned>(pc.jt0);
     }

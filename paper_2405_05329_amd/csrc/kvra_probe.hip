@@ -1,0 +1,64 @@
+// Matrix-pipe probe: what a loop of nothing but v_mfma_f32_32x32x16_bf16 on register operands delivers on
+// this chip, as a function of how many compute units are busy and of the operand data.  Not part of the
+// product path: a yardstick for reading the roofline fractions of the attention and linear kernels (the
+// published 2.5 PFLOP/s assumes 2.4 GHz on every matrix pipe at once; the clock under load is managed).
+// Built as its own small library (python -m paper_2405_05329_amd.build --probe), driven by probe.py.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// Every wave: 4 accumulators, 4 A and 4 B fragments (lane-wise 16 bytes each from `operands`), `iters`
+// rounds of 16 MFMAs (every A with every B, so consecutive MFMAs see different operands and independent
+// accumulators).  96 KiB of dynamic LDS per workgroup keeps it to one workgroup per compute unit.
+__global__ __launch_bounds__(512, 1) void probe_mfma_kernel(const bf16x8* operands, float* sink, int iters) {
+  extern __shared__ char lds[];
+  const int lane = threadIdx.x & 63;
+  bf16x8 a[4], b[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    a[i] = operands[i * 64 + lane];
+    b[i] = operands[(4 + i) * 64 + lane];
+  }
+  f32x16 acc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[i][e] = 0.0f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(i + j) & 3], b[i], acc[i], 0, 0, 0);
+  }
+  float r = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) r += acc[i][e];
+  if (iters < 0) lds[threadIdx.x] = 0;   // (never true: keeps the LDS allocation referenced)
+  sink[static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x] = r;
+}
+
+}  // namespace
+
+// operands: device, 8 x 64 x 16 bytes (4 A and 4 B fragments per lane, bf16); sink: device,
+// workgroups * 64 * waves floats.  waves in 1..8 (waves per workgroup: 4 = one per SIMD, 8 = two).
+// One workgroup per compute unit.  Returns 0, or -1 on bad arguments, or the HIP error code of the launch.
+extern "C" int kvra_probe_mfma(const void* operands, void* sink, int workgroups, int waves, int iters, void* stream) {
+  if (operands == nullptr || sink == nullptr || workgroups < 1 || waves < 1 || waves > 8 || iters < 1) return -1;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(probe_mfma_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+    if (e != hipSuccess) return static_cast<int>(e);
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(probe_mfma_kernel, dim3(workgroups), dim3(64 * waves), 96 * 1024, static_cast<hipStream_t>(stream),
+                     static_cast<const bf16x8*>(operands), static_cast<float*>(sink), iters);
+  return static_cast<int>(hipGetLastError());
+}

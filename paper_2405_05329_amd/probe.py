@@ -1,0 +1,70 @@
+"""What the matrix pipes deliver on this GPU with nothing else in the way: a loop of v_mfma_f32_32x32x16_bf16 on
+register operands, timed for several numbers of busy compute units, one or two waves per SIMD, and operand
+data of three kinds (zeros, ones, N(0,1) values).  A yardstick for the roofline fractions of the product
+kernels: 32768 FLOP per MFMA and 8 passes of 4 cycles give 4096 FLOP per cycle and compute unit, which is the
+published 2.5 PFLOP/s at 2.4 GHz on 256 compute units; the "clock" column is rate / (busy CUs x 4096 FLOP),
+i.e. the clock at which pipes that never idle would deliver the measured rate.
+
+Needs the probe library: python -m paper_2405_05329_amd.build --probe
+Usage: python -m paper_2405_05329_amd.probe [--iters 20000]
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import os
+import sys
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--iters", type=int, default=20000)
+    args = ap.parse_args()
+    import torch
+
+    lib = ctypes.CDLL(os.path.join(os.path.dirname(os.path.abspath(__file__)), "libkvra_probe.so"))
+    vp, i32 = ctypes.c_void_p, ctypes.c_int
+    lib.kvra_probe_mfma.restype = i32
+    lib.kvra_probe_mfma.argtypes = [vp, vp, i32, i32, i32, vp]
+    torch.cuda.set_device(0)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    g = torch.Generator(device="cuda")
+    g.manual_seed(0)
+    data = {
+        "zeros": torch.zeros((8, 64, 8), dtype=torch.bfloat16, device="cuda"),
+        "ones": torch.ones((8, 64, 8), dtype=torch.bfloat16, device="cuda"),
+        "N(0,1)": torch.randn((8, 64, 8), device="cuda", generator=g).to(torch.bfloat16),
+    }
+    sink = torch.empty(cus * 512, dtype=torch.float32, device="cuda")
+    print(f"device with {cus} CUs; {args.iters} x 16 MFMAs per wave; one workgroup per CU")
+    print()
+    print("| busy CUs | waves per SIMD | operands | ms | TFLOP/s | % of 2.5 PFLOP/s x busy/256 | clock GHz |")
+    print("|---|---|---|---|---|---|---|")
+    for wgs in (cus, cus * 3 // 4, cus // 2, cus // 4):
+        for waves in (4, 8):
+            for name, ops in data.items():
+                times = []
+                for rep in range(4):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    rc = lib.kvra_probe_mfma(ops.data_ptr(), sink.data_ptr(), wgs, waves, args.iters, None)
+                    assert rc == 0, rc
+                    e1.record()
+                    torch.cuda.synchronize()
+                    if rep:
+                        times.append(e0.elapsed_time(e1))
+                ms = float(np.median(times))
+                flop = wgs * waves * args.iters * 16 * 32768.0
+                rate = flop / (ms * 1e-3)
+                print(f"| {wgs} | {waves // 4} | {name} | {ms:.2f} | {rate / 1e12:.0f} | "
+                      f"{100 * rate / (2.5e15 * wgs / 256):.0f} | {rate / (wgs * 4096.0) / 1e9:.2f} |")
+
+
+if __name__ == "__main__":
+    main()
