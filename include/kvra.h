@@ -17,15 +17,16 @@
  *     reads key/value head h / (n_q_heads / n_kv_heads).
  *   - The only state the library keeps is one scratch buffer per device (about 100 MB, hipMalloc'ed
  *     by the first kvra_chunk_attn call on that device that is allowed to allocate, kept until the
- *     process ends).  It holds the partial results of key-split launches, which kvra_chunk_attn
- *     takes when the (kv head, 256-row tile) units of a call do not fill the last round of the
- *     device's CUs - e.g. a short chunk behind a long prefix.  While there is no buffer - the
- *     allocation failed, or `stream` is being captured into a graph, where allocating is illegal -
- *     a call runs without key-splitting (same results up to rounding order, slower on such shapes)
- *     and the next call tries again; to have key-split launches inside a captured graph, make one
- *     kvra_chunk_attn call on the device before the capture starts.  The buffer belongs to the
+ *     process ends).  It holds the partial results and merge counters of row tiles that
+ *     kvra_chunk_attn cuts along the keys, which it does whenever the (kv head, 256-row tile) units
+ *     of a call do not divide evenly over the device's CUs - e.g. a short chunk behind a long
+ *     prefix, or 160 units on 256 CUs.  While there is no buffer - the allocation failed, or
+ *     `stream` is being captured into a graph, where allocating is illegal - a call runs whole
+ *     units only (same results up to rounding order, slower on such shapes) and the next call
+ *     tries again; to have cut units inside a captured graph, make one kvra_chunk_attn call on the
+ *     device before the capture starts, or use kvra_chunk_attn_noalloc.  The buffer belongs to the
  *     device that is current when the call is made, which must be the device of `stream`.
- *     Two key-split calls (kvra_layer_chunk included) that overlap in time on one device, from
+ *     Two calls that cut units (kvra_layer_chunk included) and overlap in time on one device, from
  *     different streams, share the buffer and race: not supported, not detected.
  */
 #ifndef KVRA_H
@@ -100,7 +101,7 @@ int kvra_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
  * kvra_chunk_attn for callers that cannot allocate device memory: code that runs under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same
  * launch plan and therefore the same results bit for bit; it calls no hipMalloc / hipFree and no
- * allocating library routine.  The partial results of key-split launches go to a fixed array in the
+ * allocating library routine.  The partial results and counters of cut units go to a fixed array in the
  * library's device image instead of the allocated buffer: kvra_chunk_attn_noalloc_scratch_bytes()
  * bytes (99 MiB = 768 partial-result slots, three per compute unit of a 256-CU device), which every
  * GPU the library is loaded on holds until the process ends.  Its device address is looked up on the
@@ -108,9 +109,9 @@ int kvra_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
  *   - A call whose launch plan (kvra_chunk_attn_plan with the device's CU count) needs more than
  *     that - possible only on a device with more than 256 CUs - returns KVRA_ESCRATCH and enqueues
  *     nothing.  KVRA_ENODEVICE: the array's address could not be obtained.
- *   - Nothing in the array has to start at zero (every slot is written in full by the kernel before
- *     the merge kernel reads it), so calls need no clearing in between; the contents after a call
- *     are scratch.
+ *   - Calls need no clearing in between: a partial-result slot is written in full before the piece
+ *     that merges its row tile reads it, and the merge counters (zero when the library is loaded)
+ *     are set back to zero by every merge.  The other contents after a call are scratch.
  *   - All calls on one GPU share the array: two calls that overlap in time on one device (different
  *     streams, or two graphs replayed concurrently) race.  Calls on one stream are ordered and safe.
  */

@@ -21,7 +21,10 @@ What it defines
     every layer waits for the precedent's cache (Sec. 4 overview, Fig. 5(b));
   * the decoder layer a process runs around the attention block (App. C listing: q/k/v and
     output projections; RMSNorm and the SwiGLU MLP come from the LLaMA models of Sec. 5),
-    exact or with bf16 storage rounding of every intermediate tensor.
+    exact or with bf16 storage rounding of every intermediate tensor; and the same layer evaluated for a
+    few rows of a long context only (layer_kv_cache: K, V of every token; decoder_layer_rows: the rest of
+    the layer for the chosen rows), which is the definition again with the rows that are not asked for
+    left out, pinned against decoder_layer on a small case.
 
 Pinned by tests/test_oracle_*.py against hand-computed rationals, closed forms,
 torch's CPU scaled_dot_product_attention / rms_norm / silu / linear, the paper's worked

@@ -31,13 +31,15 @@
 // block costs issue time the matrix pipe of the partner wave waits for, scalar ones included, and
 // v_dot2c_f32_bf16 queues behind the partner's MFMAs: the block is kept to exp2, add and convert.
 //
-// Launch shapes.  Normally one workgroup per unit (kv head, 256-row tile), every unit whole.  When
-// the units do not fill the last round of CUs (160 or 320 units on 256 CUs; a handful of very long
-// units for a short chunk behind a long prefix), the units of that round are cut into S equal key
-// segments each, one workgroup per segment, issued segment by segment so that the row tiles of a
-// head still sweep the same keys at the same time (which is what lets them share the K/V stream in
-// L2).  The un-normalised pieces go through a per-device scratch buffer to a small fix-up kernel
-// that merges them (the usual log-sum-exp merge).
+// Launch shape.  A unit is one 256-row tile of one kv head against all the key tiles it sees.  A launch is
+// one persistent kernel, one workgroup per compute unit, that walks a schedule made on the host
+// (plan_chunk_attn): the workgroups form groups (one per XCD, each with its own kv heads), a slot of a
+// group runs whole units of the complete rounds and then its share of what does not fill a round - leftover
+// units and, when there is at most one complete round, the tails of the first round's units cut at a common
+// length - so that every slot ends up with the same number of tile steps.  A piece that is not a whole unit
+// leaves its un-normalised (O, m, l) in a scratch slot with device-coherent stores and adds its tile steps
+// to the unit's counter; the piece that completes the count merges the unit's partial results in a fixed
+// order (the usual log-sum-exp merge) and writes the rows.  No workgroup waits for another one.
 #include "kvra_internal.h"
 
 #include <algorithm>

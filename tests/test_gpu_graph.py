@@ -1,6 +1,6 @@
 """The library under HIP graph capture.
 
-Every entry point is asynchronous on the caller's stream and, once the key-split scratch of
+Every entry point is asynchronous on the caller's stream and, once the scratch buffer of
 kvra_chunk_attn exists (it is allocated on the first call on a device), allocates nothing: a whole
 chunk sequence then records into a graph.  Each replay has to reproduce the eager result bit for
 bit (the kernels are deterministic); eager work and synchronisations run between the replays.
@@ -26,7 +26,7 @@ def _sequence(q, q_master, k_in, v_in, k_cache, v_cache, out, bounds, H, Hkv, d,
 
 
 @pytest.mark.parametrize("H,Hkv,d,bounds", [
-    (8, 8, 128, [0, 2400, 2700, 3000]),      # chunks 1 and 2: 16 units behind 2400+ keys -> key-split launches
+    (8, 8, 128, [0, 2400, 2700, 3000]),      # chunks 1 and 2: 16 units behind 2400+ keys -> cut units, merged in the kernel
     (8, 2, 64, [0, 1111, 1500]),
 ])
 def test_chunk_sequence_replays_from_a_graph(H, Hkv, d, bounds):

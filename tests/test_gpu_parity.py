@@ -340,7 +340,7 @@ def test_long_context_sampled_rows():
 
 @pytest.mark.parametrize("H,Hkv,d,prefix,c", [(32, 32, 128, 20000, 8), (8, 8, 64, 12345, 1), (32, 8, 128, 3000, 1280),
                                                (71, 1, 64, 9000, 300)])
-def test_key_split_launch_shapes(H, Hkv, d, prefix, c):
+def test_cut_unit_launch_shapes(H, Hkv, d, prefix, c):
     """Shapes whose few (or unevenly many) work units make the library cut them along the keys:
     a short chunk behind a long prefix (down to a single token), and unit counts between one and
     two rounds of CUs.  Every row of the chunk is checked."""
@@ -348,8 +348,8 @@ def test_key_split_launch_shapes(H, Hkv, d, prefix, c):
     q, k, v, scale, res = _run(32, 1, C, H, Hkv, d, [0, prefix, C])
     rows = list(range(prefix, C))
     want = orc.attention_rows(_f64(q), _f64(k), _f64(v), rows, scale, rope_base=synth.ROPE_BASE)
-    mx, mean = _check_out(res["out"][rows], want, f"key-split {H}/{Hkv} d{d} prefix {prefix} c {c}")
-    print(f"key-split {H}/{Hkv} d{d} prefix {prefix} c {c}: max-abs {mx:.3e} mean-abs {mean:.3e}")
+    mx, mean = _check_out(res["out"][rows], want, f"cut units {H}/{Hkv} d{d} prefix {prefix} c {c}")
+    print(f"cut units {H}/{Hkv} d{d} prefix {prefix} c {c}: max-abs {mx:.3e} mean-abs {mean:.3e}")
 
 
 def _random_cases(n, seed):
