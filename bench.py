@@ -334,22 +334,38 @@ def main():
     out = torch.empty((C, H, d), dtype=torch.bfloat16, device="cuda")
     stream = torch.cuda.current_stream()
 
+    # Two events per chunk, around the attention call (every event costs about 3.5 us of stream time, so none
+    # is spent on the append: its time is the stretch from the previous chunk's end event to this chunk's
+    # start event, and a chunk's time - append + attention - runs from end event to end event).
     def run_step(bnds, qw, events=None, stream=stream):
         for i in range(len(bnds) - 1):
             lo, hi = bnds[i], bnds[i + 1]
-            if events is not None:
-                events[i][0].record(stream)
             kvra.kvra_append_kv(k_in[lo:hi], v_in[lo:hi], qw[lo:hi], k_cache, v_cache, lo, hi - lo, C,
                                 H, Hkv, d, synth.ROPE_BASE, stream=stream)
             if events is not None:
-                events[i][1].record(stream)
+                events[i][0].record(stream)
             kvra.kvra_chunk_attn(qw[lo:hi], k_cache, v_cache, lo, hi - lo, H, Hkv, d, scale, out[lo:hi],
                                  stream=stream)
             if events is not None:
-                events[i][2].record(stream)
+                events[i][1].record(stream)
 
     def new_events(n):
-        return [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n)]
+        return [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(n)]
+
+    def chunk_times(first, passes):
+        """(append ms, attention ms) per pass and chunk from the events of consecutive passes; `first` is the
+        event recorded just before the first pass."""
+        app, att = [], []
+        prev = first
+        for e in passes:
+            a_row, t_row = [], []
+            for pair in e:
+                a_row.append(prev.elapsed_time(pair[0]))
+                t_row.append(pair[0].elapsed_time(pair[1]))
+                prev = pair[1]
+            app.append(a_row)
+            att.append(t_row)
+        return np.array(app), np.array(att)
 
     if args.calib_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
@@ -365,8 +381,10 @@ def main():
         if s >= n_buf:
             q_work[s % n_buf].copy_(q_master)
     ev = [new_events(p) for _ in range(args.steps)]
+    first_ev = torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    first_ev.record(stream)
     for s in range(args.steps):
         run_step(bounds, q_work[(args.warmup + s) % n_buf], ev[s])
     torch.cuda.synchronize()
@@ -375,8 +393,7 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
     flops_chunk = [useful_flops(bounds[i], bounds[i + 1] - bounds[i], H, d) for i in range(p)]
     flops_step = sum(flops_chunk)
-    append_ms = np.array([[e[0].elapsed_time(e[1]) for e in step] for step in ev])   # [steps, p]
-    attn_ms = np.array([[e[1].elapsed_time(e[2]) for e in step] for step in ev])
+    append_ms, attn_ms = chunk_times(first_ev, ev)   # [steps, p]
     attn_mean = attn_ms.mean(axis=0)
     append_mean = append_ms.mean(axis=0)
     attn_avg_launch_ms = float(attn_ms.mean())
@@ -404,7 +421,8 @@ def main():
                      "algorithmic_bytes": algorithmic_bytes,
                      "traffic_over_algorithmic": traffic["bytes"] / algorithmic_bytes if traffic else None,
                      "avg_launch_ms": attn_avg_launch_ms,
-                     "timing": "HIP events on the launch stream around every kvra_chunk_attn call of the timed steps"},
+                     "timing": "HIP events on the launch stream around every kvra_chunk_attn call of the timed steps; the append "
+                               "is timed from the previous call's end event to this call's start event"},
         "per_chunk": {"attn_ms": [round(float(x), 4) for x in attn_mean],
                       "attn_ms_median": [round(float(x), 4) for x in np.median(attn_ms, axis=0)],
                       "attn_ms_min": [round(float(x), 4) for x in attn_ms.min(axis=0)],
@@ -422,19 +440,20 @@ def main():
     def measured_chunks(bnds):
         """Mean per-chunk (append ms, append + attention ms) of a partition over `reps` passes."""
         n = len(bnds) - 1
-        tot, app = np.zeros(n), np.zeros(n)
         # untimed passes first: after host-side work (the search) the GPU has been idle, and the first
         # milliseconds of work after an idle period run at lower clocks (15 % slower launches measured)
         for rep in range(8):
             run_step(bnds, q_work[rep % n_buf])
         for rep in range(reps):
-            qw = q_work[rep % n_buf]
-            qw.copy_(q_master)
-            e = new_events(n)
-            run_step(bnds, qw, e)
-            torch.cuda.synchronize()
-            tot += np.array([x[0].elapsed_time(x[2]) for x in e])
-            app += np.array([x[0].elapsed_time(x[1]) for x in e])
+            q_work[rep % n_buf].copy_(q_master)
+        first = torch.cuda.Event(enable_timing=True)
+        passes = [new_events(n) for _ in range(reps)]
+        first.record(stream)
+        for rep in range(reps):
+            run_step(bnds, q_work[rep % n_buf], passes[rep])
+        torch.cuda.synchronize()
+        a_ms, t_ms = chunk_times(first, passes)
+        app, tot = a_ms.sum(axis=0), (a_ms + t_ms).sum(axis=0)
         return app / reps, tot / reps
 
     if not (args.no_makespan or args.no_extras):
@@ -455,23 +474,21 @@ def main():
         def measure(prefix, c):
             # back to back, as in a step: a launch timed alone, with the chip idle before and after it, runs
             # at higher clocks than the same launch in a stream of work (10 - 20 % on these boxes)
-            # (and with the same events around and between the two launches as the makespan measurement has)
+            # (and with the same two events per pair of launches as the makespan measurement has)
             n_rep = 6
-            evs = new_events(n_rep)
+            evs = new_events(n_rep + 1)
             for rep in range(n_rep + 2):
-                timed = rep >= 2
-                if timed:
-                    evs[rep - 2][0].record(stream)
                 kvra.kvra_append_kv(k_in[prefix:prefix + c], v_in[prefix:prefix + c], qw[prefix:prefix + c], k_cache,
                                     v_cache, prefix, c, C, H, Hkv, d, synth.ROPE_BASE, stream=stream)
-                if timed:
-                    evs[rep - 2][1].record(stream)
+                if rep >= 1:
+                    evs[rep - 1][0].record(stream)
                 kvra.kvra_chunk_attn(qw[prefix:prefix + c], k_cache, v_cache, prefix, c, H, Hkv, d, scale,
                                      out[prefix:prefix + c], stream=stream)
-                if timed:
-                    evs[rep - 2][2].record(stream)
+                if rep >= 1:
+                    evs[rep - 1][1].record(stream)
             torch.cuda.synchronize()
-            return float(np.mean([e[0].elapsed_time(e[2]) for e in evs]))
+            # end event to end event: one append + one attention, as a chunk of a step is timed
+            return float(np.mean([evs[j][1].elapsed_time(evs[j + 1][1]) for j in range(n_rep)]))
 
         def features(prefix, c):
             pl = kvra.kvra_chunk_attn_plan(prefix, c, H, Hkv, d, cus)
