@@ -15,8 +15,10 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 // Every wave: 4 accumulators, 4 A and 4 B fragments (lane-wise 16 bytes each from `operands`), `iters`
 // rounds of 16 MFMAs (every A with every B, so consecutive MFMAs see different operands and independent
 // accumulators).  96 KiB of dynamic LDS per workgroup keeps it to one workgroup per compute unit.
-__global__ __launch_bounds__(512, 1) void probe_mfma_kernel(const bf16x8* operands, float* sink, int iters) {
+__global__ __launch_bounds__(512, 1) void probe_mfma_kernel(const bf16x8* operands, float* sink, int iters,
+                                                            unsigned long long* stamps) {
   extern __shared__ char lds[];
+  const unsigned long long t0 = wall_clock64();
   const int lane = threadIdx.x & 63;
   bf16x8 a[4], b[4];
 #pragma unroll
@@ -29,11 +31,15 @@ __global__ __launch_bounds__(512, 1) void probe_mfma_kernel(const bf16x8* operan
   for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[i][e] = 0.0f;
-  for (int it = 0; it < iters; ++it) {
+  // (four rounds per trip: a 16-instruction loop body was found to run a third slower with two waves per SIMD
+  // in one build than in the next, with identical instructions - instruction fetch at the loop's edges)
+  for (int it = 0; it < iters / 4; ++it) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int u = 0; u < 4; ++u)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(i + j) & 3], b[i], acc[i], 0, 0, 0);
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(i + j) & 3], b[i], acc[i], 0, 0, 0);
   }
   float r = 0.0f;
 #pragma unroll
@@ -42,15 +48,25 @@ __global__ __launch_bounds__(512, 1) void probe_mfma_kernel(const bf16x8* operan
     for (int e = 0; e < 16; ++e) r += acc[i][e];
   if (iters < 0) lds[threadIdx.x] = 0;   // (never true: keeps the LDS allocation referenced)
   sink[static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x] = r;
+  // per workgroup: XCD it ran on, start and end of the constant 100 MHz clock
+  if (stamps != nullptr && threadIdx.x == 0) {
+    unsigned xcc;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+    stamps[3 * blockIdx.x + 0] = xcc & 0xF;
+    stamps[3 * blockIdx.x + 1] = t0;
+    stamps[3 * blockIdx.x + 2] = wall_clock64();
+  }
 }
 
 }  // namespace
 
 // operands: device, 8 x 64 x 16 bytes (4 A and 4 B fragments per lane, bf16); sink: device,
-// workgroups * 64 * waves floats.  waves in 1..8 (waves per workgroup: 4 = one per SIMD, 8 = two).
-// One workgroup per compute unit.  Returns 0, or -1 on bad arguments, or the HIP error code of the launch.
-extern "C" int kvra_probe_mfma(const void* operands, void* sink, int workgroups, int waves, int iters, void* stream) {
-  if (operands == nullptr || sink == nullptr || workgroups < 1 || waves < 1 || waves > 8 || iters < 1) return -1;
+// workgroups * 64 * waves floats; stamps: device, 3 * workgroups 64-bit words (XCD, start, end per workgroup),
+// or NULL.  waves in 1..8 (waves per workgroup: 4 = one per SIMD, 8 = two).
+// iters: rounds of 16 MFMAs per wave, a multiple of 4.  One workgroup per compute unit.  Returns 0, or -1 on bad arguments, or the HIP error code of the launch.
+extern "C" int kvra_probe_mfma(const void* operands, void* sink, int workgroups, int waves, int iters, void* stamps,
+                               void* stream) {
+  if (operands == nullptr || sink == nullptr || workgroups < 1 || waves < 1 || waves > 8 || iters < 4 || iters % 4 != 0) return -1;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(probe_mfma_kernel),
@@ -59,6 +75,7 @@ extern "C" int kvra_probe_mfma(const void* operands, void* sink, int workgroups,
     attr_set = true;
   }
   hipLaunchKernelGGL(probe_mfma_kernel, dim3(workgroups), dim3(64 * waves), 96 * 1024, static_cast<hipStream_t>(stream),
-                     static_cast<const bf16x8*>(operands), static_cast<float*>(sink), iters);
+                     static_cast<const bf16x8*>(operands), static_cast<float*>(sink), iters,
+                     static_cast<unsigned long long*>(stamps));
   return static_cast<int>(hipGetLastError());
 }

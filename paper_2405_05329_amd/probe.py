@@ -31,7 +31,7 @@ def main():
     lib = ctypes.CDLL(os.path.join(os.path.dirname(os.path.abspath(__file__)), "libkvra_probe.so"))
     vp, i32 = ctypes.c_void_p, ctypes.c_int
     lib.kvra_probe_mfma.restype = i32
-    lib.kvra_probe_mfma.argtypes = [vp, vp, i32, i32, i32, vp]
+    lib.kvra_probe_mfma.argtypes = [vp, vp, i32, i32, i32, vp, vp]
     torch.cuda.set_device(0)
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     g = torch.Generator(device="cuda")
@@ -53,7 +53,7 @@ def main():
                 for rep in range(4):
                     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                     e0.record()
-                    rc = lib.kvra_probe_mfma(ops.data_ptr(), sink.data_ptr(), wgs, waves, args.iters, None)
+                    rc = lib.kvra_probe_mfma(ops.data_ptr(), sink.data_ptr(), wgs, waves, args.iters, None, None)
                     assert rc == 0, rc
                     e1.record()
                     torch.cuda.synchronize()
@@ -64,6 +64,24 @@ def main():
                 rate = flop / (ms * 1e-3)
                 print(f"| {wgs} | {waves // 4} | {name} | {ms:.2f} | {rate / 1e12:.0f} | "
                       f"{100 * rate / (2.5e15 * wgs / 256):.0f} | {rate / (wgs * 4096.0) / 1e9:.2f} |")
+
+    # the same loop on all CUs, N(0,1) operands, two waves per SIMD, with per-workgroup stamps: do the XCDs differ?
+    stamps = torch.zeros((cus, 3), dtype=torch.int64, device="cuda")
+    for rep in range(2):
+        rc = lib.kvra_probe_mfma(data["N(0,1)"].data_ptr(), sink.data_ptr(), cus, 8, args.iters, stamps.data_ptr(), None)
+        assert rc == 0, rc
+        torch.cuda.synchronize()
+    st = stamps.cpu().numpy()
+    dur = (st[:, 2] - st[:, 1]) * 0.01          # us
+    print()
+    print(f"per XCD, {cus} busy CUs, N(0,1) operands: mean workgroup time in us (workgroups), relative to the fastest XCD")
+    print()
+    print("| XCD | workgroups | mean us | relative |")
+    print("|---|---|---|---|")
+    means = {int(x): float(dur[st[:, 0] == x].mean()) for x in np.unique(st[:, 0])}
+    fastest = min(means.values())
+    for x, m in sorted(means.items()):
+        print(f"| {x} | {int((st[:, 0] == x).sum())} | {m:.1f} | {m / fastest:.3f} |")
 
 
 if __name__ == "__main__":
