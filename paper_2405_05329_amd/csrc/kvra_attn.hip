@@ -103,11 +103,16 @@ struct AttnArgs {
 #ifdef KVRA_TRACE
 // Timeline build (python -m paper_2405_05329_amd.build --trace): every workgroup leaves time stamps of the
 // constant 100 MHz clock - entry, first tile step, last tile step done, exit - with the compute unit it
-// ran on and its number of tile steps, for the accounting of where a launch's time goes.
-constexpr int kTraceWords = 8;
+// ran on, its number of tile steps and the shader-clock cycle counter at both ends of the tile loop, for the
+// accounting of where a launch's time goes.
+constexpr int kTraceWords = 10;
 constexpr int kTracePieces = 8;   // pieces of a workgroup that leave stamps
 __device__ __forceinline__ void trace_stamp(unsigned long long* rec, int word) {
-  if (rec != nullptr && threadIdx.x == 0) rec[word] = wall_clock64();
+  if (rec != nullptr && threadIdx.x == 0) {
+    rec[word] = wall_clock64();
+    // around the tile loop also the shader-clock cycle counter: cycles / time = the clock the loop ran at
+    if (word == 1 || word == 2) rec[7 + word] = clock64();
+  }
 }
 #define KVRA_TRACE_STAMP(rec, word) trace_stamp(rec, word)
 #else

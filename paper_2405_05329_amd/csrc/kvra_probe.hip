@@ -19,6 +19,7 @@ __global__ __launch_bounds__(512, 1) void probe_mfma_kernel(const bf16x8* operan
                                                             unsigned long long* stamps) {
   extern __shared__ char lds[];
   const unsigned long long t0 = wall_clock64();
+  const unsigned long long c0 = clock64();
   const int lane = threadIdx.x & 63;
   bf16x8 a[4], b[4];
 #pragma unroll
@@ -48,20 +49,22 @@ __global__ __launch_bounds__(512, 1) void probe_mfma_kernel(const bf16x8* operan
     for (int e = 0; e < 16; ++e) r += acc[i][e];
   if (iters < 0) lds[threadIdx.x] = 0;   // (never true: keeps the LDS allocation referenced)
   sink[static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x] = r;
-  // per workgroup: XCD it ran on, start and end of the constant 100 MHz clock
-  if (stamps != nullptr && threadIdx.x == 0) {
+  // per wave: XCD it ran on, start and end of the constant 100 MHz clock, cycles of the shader clock
+  if (stamps != nullptr && lane == 0) {
     unsigned xcc;
     asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
-    stamps[3 * blockIdx.x + 0] = xcc & 0xF;
-    stamps[3 * blockIdx.x + 1] = t0;
-    stamps[3 * blockIdx.x + 2] = wall_clock64();
+    unsigned long long* rec = stamps + 4 * (static_cast<size_t>(blockIdx.x) * (blockDim.x / 64) + threadIdx.x / 64);
+    rec[0] = xcc & 0xF;
+    rec[1] = t0;
+    rec[2] = wall_clock64();
+    rec[3] = clock64() - c0;
   }
 }
 
 }  // namespace
 
 // operands: device, 8 x 64 x 16 bytes (4 A and 4 B fragments per lane, bf16); sink: device,
-// workgroups * 64 * waves floats; stamps: device, 3 * workgroups 64-bit words (XCD, start, end per workgroup),
+// workgroups * 64 * waves floats; stamps: device, 4 * workgroups * waves 64-bit words (XCD, start, end, shader-clock cycles per wave),
 // or NULL.  waves in 1..8 (waves per workgroup: 4 = one per SIMD, 8 = two).
 // iters: rounds of 16 MFMAs per wave, a multiple of 4.  One workgroup per compute unit.  Returns 0, or -1 on bad arguments, or the HIP error code of the launch.
 extern "C" int kvra_probe_mfma(const void* operands, void* sink, int workgroups, int waves, int iters, void* stamps,

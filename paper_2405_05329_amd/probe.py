@@ -65,23 +65,29 @@ def main():
                 print(f"| {wgs} | {waves // 4} | {name} | {ms:.2f} | {rate / 1e12:.0f} | "
                       f"{100 * rate / (2.5e15 * wgs / 256):.0f} | {rate / (wgs * 4096.0) / 1e9:.2f} |")
 
-    # the same loop on all CUs, N(0,1) operands, two waves per SIMD, with per-workgroup stamps: do the XCDs differ?
-    stamps = torch.zeros((cus, 3), dtype=torch.int64, device="cuda")
+    # the same loop on all CUs, N(0,1) operands, two waves per SIMD, with per-workgroup stamps: do the XCDs differ,
+    # and does the shader-clock cycle counter (which timeline.py uses) agree with the clock the MFMA count implies?
+    stamps = torch.zeros((cus, 8, 4), dtype=torch.int64, device="cuda")
     for rep in range(2):
         rc = lib.kvra_probe_mfma(data["N(0,1)"].data_ptr(), sink.data_ptr(), cus, 8, args.iters, stamps.data_ptr(), None)
         assert rc == 0, rc
         torch.cuda.synchronize()
     st = stamps.cpu().numpy()
-    dur = (st[:, 2] - st[:, 1]) * 0.01          # us
+    xcd = st[:, 0, 0]
+    dur = (st[:, :, 2].max(axis=1) - st[:, :, 1].min(axis=1)) * 0.01          # us, first wave in to last wave out
+    cycles = st[:, :, 3].max(axis=1)
     print()
-    print(f"per XCD, {cus} busy CUs, N(0,1) operands: mean workgroup time in us (workgroups), relative to the fastest XCD")
+    print(f"per XCD, {cus} busy CUs, N(0,1) operands, two waves per SIMD: mean workgroup time in us, relative to the fastest XCD")
     print()
-    print("| XCD | workgroups | mean us | relative |")
-    print("|---|---|---|---|")
-    means = {int(x): float(dur[st[:, 0] == x].mean()) for x in np.unique(st[:, 0])}
+    print("| XCD | workgroups | mean us | relative | GHz by the cycle counter | GHz by the MFMA count |")
+    print("|---|---|---|---|---|---|")
+    means = {int(x): float(dur[xcd == x].mean()) for x in np.unique(xcd)}
     fastest = min(means.values())
     for x, m in sorted(means.items()):
-        print(f"| {x} | {int((st[:, 0] == x).sum())} | {m:.1f} | {m / fastest:.3f} |")
+        sel = xcd == x
+        by_counter = float((cycles[sel] / dur[sel]).mean()) / 1e3
+        by_count = 2 * args.iters * 16 * 32 / m / 1e3      # two waves per SIMD, 32 cycles per MFMA
+        print(f"| {x} | {int(sel.sum())} | {m:.1f} | {m / fastest:.3f} | {by_counter:.2f} | {by_count:.2f} |")
 
 
 if __name__ == "__main__":

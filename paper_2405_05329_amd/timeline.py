@@ -13,6 +13,8 @@ tile step done and its end, together with the compute unit it ran on.  For every
   steps      time the CUs spent inside tile loops, averaged over CUs (differs from `ideal` where pieces run
              partly filled row tiles, or slower than the median: first and last steps of a piece)
   step med   median over the pieces of (time in the tile loop / tile steps)
+  GHz        median over the pieces of (shader-clock cycles in the tile loop / time in it): the clock the loop ran
+             at; cycles per step = step med x GHz, against the 2048 matrix-pipe cycles of a step
   pro/epi    time between a piece's start and its first step, and between its last step and its end (the
              merge of a cut unit is part of the last piece's epi), per CU
   gap        time a CU sat between two pieces, per CU
@@ -42,7 +44,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-TRACE_WORDS = 8
+TRACE_WORDS = 10
 TRACE_PIECES = 8   # pieces per workgroup that leave stamps
 TICK_US = 0.01   # 100 MHz
 
@@ -160,10 +162,13 @@ def main():
         pro = float(np.sum(loop0 - enter)) / n_cu
         epi = float(np.sum(exit_ - loop1)) / n_cu
         per_step = (loop1 - loop0) / np.maximum(steps, 1.0)
+        loop_cycles = (t[:, 9] - t[:, 8]).astype(np.float64)
+        ok = (loop1 - loop0) > 5.0                 # pieces long enough for the two clocks to be compared
+        ghz = float(np.median(loop_cycles[ok] / (loop1 - loop0)[ok]) / 1e3) if ok.any() else 0.0
         rows.append(dict(chunk=i, prefix=lo, c=c, groups=len(steps), plan=plan, launch=launch_us, span=span,
                          total_steps=float(steps.sum()), in_steps=in_steps, pro=pro, epi=epi, gap=gap / n_cu,
                          ramp=(ramp + idle_cus * span) / n_cu, tail=tail / n_cu, idle_cus=idle_cus,
-                         step_med=float(np.median(per_step)), cus_used=len(keys),
+                         step_med=float(np.median(per_step)), cus_used=len(keys), ghz=ghz,
                          entry=float(entry_to_start[entry_to_start > 0].mean()) if (entry_to_start > 0).any() else 0.0))
     flops = lambda lo, c: 4 * d * H * (c * lo + c * (c + 1) // 2)
     print(f"workload {args.workload}: {H}/{Hkv} heads x {d}, context {C}; device with {cus} CUs; times in us")
@@ -171,8 +176,8 @@ def main():
           f"{rows[0]['plan']['key_tile']} keys x {rows[0]['plan']['rows_per_tile']} rows; "
           "2048 matrix-pipe cycles per SIMD at head_dim 128 and 64 alike")
     print()
-    print("| chunk | prefix | c | units, pieces | row tile | launch | TFLOP/s | span | ideal | steps | pro | epi | gap | ramp | tail | launch - span | entry | step med |")
-    print("|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|")
+    print("| chunk | prefix | c | units, pieces | row tile | launch | TFLOP/s | span | ideal | steps | pro | epi | gap | ramp | tail | launch - span | entry | step med | GHz | cycles per step |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|")
     for r in rows:
         p = r["plan"]
         shape = f"{p['units'] * p['groups']} u, {r['groups']} p" + (f", {p['partial_pieces']} merged" if p["partial_pieces"] else "")
@@ -180,7 +185,7 @@ def main():
         print(f"| {r['chunk']} | {r['prefix']} | {r['c']} | {shape} | {p['rows_per_tile']} | {r['launch']:.1f} | "
               f"{flops(r['prefix'], r['c']) / r['launch'] / 1e6:.0f} | {r['span']:.1f} | {ideal:.1f} | {r['in_steps']:.1f} | "
               f"{r['pro']:.1f} | {r['epi']:.1f} | {r['gap']:.1f} | {r['ramp']:.1f} | {r['tail']:.1f} | "
-              f"{r['launch'] - r['span']:.1f} | {r['entry']:.1f} | {r['step_med']:.3f} |")
+              f"{r['launch'] - r['span']:.1f} | {r['entry']:.1f} | {r['step_med']:.3f} | {r['ghz']:.2f} | {r['step_med'] * r['ghz'] * 1e3:.0f} |")
     tot_launch = sum(r["launch"] for r in rows)
     tot_ideal = sum(r["total_steps"] / cus * r["step_med"] for r in rows)
     print()
