@@ -61,6 +61,62 @@ __global__ __launch_bounds__(512, 1) void probe_mfma_kernel(const bf16x8* operan
   }
 }
 
+// VALU issue probe: waves 4-7 of every workgroup (one per SIMD) run a stream of independent VALU instructions
+// - fused multiply-adds, or exponentials each followed by one - and time it with the shader-clock cycle counter,
+// while waves 0-3, their SIMD partners, are idle or issue MFMAs back to back.  cycles: one word per timed wave.
+__global__ __launch_bounds__(512, 1) void probe_valu_kernel(const bf16x8* operands, float* sink, unsigned long long* cycles,
+                                                            int valu_rounds, int with_mfma, int with_exp) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  float r = 0.0f;
+  if (wave < 4) {
+    if (with_mfma) {
+      const bf16x8 a = operands[lane], b = operands[64 + lane];
+      f32x16 acc[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][e] = 0.0f;
+      // enough MFMAs to outlast the timed waves: 64 VALU instructions take at most ~700 cycles, 16 MFMAs 512
+      for (int it = 0; it < 2 * valu_rounds; ++it) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) r += acc[i][e];
+    }
+  } else {
+    float x[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = threadIdx.x * 0.001f + i;
+    __builtin_amdgcn_s_sleep(20);   // let the partners get going
+    const unsigned long long c0 = clock64();
+    if (with_exp) {
+      for (int it = 0; it < valu_rounds; ++it) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+          for (int i = 0; i < 8; ++i) x[i] = fmaf(__builtin_amdgcn_exp2f(x[i]), 0.0f, 0.5f);
+      }
+    } else {
+      for (int it = 0; it < valu_rounds; ++it) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+          for (int i = 0; i < 8; ++i) x[i] = fmaf(x[i], 0.999f, 0.5f);
+      }
+    }
+    const unsigned long long c1 = clock64();
+#pragma unroll
+    for (int i = 0; i < 8; ++i) r += x[i];
+    if (lane == 0) cycles[blockIdx.x * 4 + (wave - 4)] = c1 - c0;
+  }
+  sink[static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x] = r;
+}
+
 }  // namespace
 
 // operands: device, 8 x 64 x 16 bytes (4 A and 4 B fragments per lane, bf16); sink: device,
@@ -80,5 +136,16 @@ extern "C" int kvra_probe_mfma(const void* operands, void* sink, int workgroups,
   hipLaunchKernelGGL(probe_mfma_kernel, dim3(workgroups), dim3(64 * waves), 96 * 1024, static_cast<hipStream_t>(stream),
                      static_cast<const bf16x8*>(operands), static_cast<float*>(sink), iters,
                      static_cast<unsigned long long*>(stamps));
+  return static_cast<int>(hipGetLastError());
+}
+
+// VALU issue probe on `workgroups` compute units: every timed wave issues valu_rounds * 64 VALU instructions
+// (64 multiply-adds, or 32 exponentials and 32 multiply-adds).  cycles: device, 4 * workgroups 64-bit words.
+extern "C" int kvra_probe_valu(const void* operands, void* sink, void* cycles, int workgroups, int valu_rounds,
+                               int with_mfma, int with_exp, void* stream) {
+  if (operands == nullptr || sink == nullptr || cycles == nullptr || workgroups < 1 || valu_rounds < 1) return -1;
+  hipLaunchKernelGGL(probe_valu_kernel, dim3(workgroups), dim3(512), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const bf16x8*>(operands), static_cast<float*>(sink),
+                     static_cast<unsigned long long*>(cycles), valu_rounds, with_mfma, with_exp);
   return static_cast<int>(hipGetLastError());
 }

@@ -90,5 +90,33 @@ def main():
         print(f"| {x} | {int(sel.sum())} | {m:.1f} | {m / fastest:.3f} | {by_counter:.2f} | {by_count:.2f} |")
 
 
+    # what a VALU instruction costs a wave while its SIMD partner is idle or issues MFMAs back to back
+    lib.kvra_probe_valu.restype = i32
+    lib.kvra_probe_valu.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp]
+    cyc = torch.zeros((cus, 4), dtype=torch.int64, device="cuda")
+    rounds = 500
+    print()
+    print(f"VALU issue: cycles per wave64 instruction of a stream of independent instructions ({rounds * 64} per wave), "
+          "one timed wave per SIMD, all CUs")
+    print()
+    print("| stream | SIMD partner | cycles per instruction |")
+    print("|---|---|---|")
+    res = {}
+    for with_exp in (0, 1):
+        for with_mfma in (0, 1):
+            for rep in range(2):
+                rc = lib.kvra_probe_valu(data["N(0,1)"].data_ptr(), sink.data_ptr(), cyc.data_ptr(), cus, rounds, with_mfma,
+                                         with_exp, None)
+                assert rc == 0, rc
+                torch.cuda.synchronize()
+            res[(with_exp, with_mfma)] = float(cyc.cpu().numpy().mean()) / (rounds * 64)
+    for with_mfma in (0, 1):
+        partner = "MFMAs back to back" if with_mfma else "idle"
+        fma = res[(0, with_mfma)]
+        mixed = res[(1, with_mfma)]
+        print(f"| v_fma_f32 | {partner} | {fma:.1f} |")
+        print(f"| v_exp_f32 (from a 1:1 mix with v_fma_f32: 2 x {mixed:.1f} - {fma:.1f}) | {partner} | {2 * mixed - fma:.1f} |")
+
+
 if __name__ == "__main__":
     main()
