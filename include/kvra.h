@@ -25,7 +25,8 @@
  *     units only (same results up to rounding order, slower on such shapes) and the next call
  *     tries again; to have cut units inside a captured graph, make one kvra_chunk_attn call on the
  *     device before the capture starts, or use kvra_chunk_attn_noalloc.  The buffer belongs to the
- *     device that is current when the call is made, which must be the device of `stream`.
+ *     device that is current when the call is made, which must be the device of `stream`
+ *     (KVRA_EINVAL if `stream` is known to belong to another device).
  *     Two calls that cut units (kvra_layer_chunk included) and overlap in time on one device, from
  *     different streams, share the buffer and race: not supported, not detected.
  */

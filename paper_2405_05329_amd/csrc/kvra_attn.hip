@@ -1115,6 +1115,16 @@ int cached_plan(int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_kv_h
 int launch_chunk_attn(const void* q, const void* k_cache, const void* v_cache,
                       int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_kv_heads, int head_dim,
                       float scale, void* out, hipStream_t stream, bool static_scratch_only) {
+  // the scratch buffer is looked up by the current device: a stream of another device would get the wrong one
+  if (stream != nullptr) {
+    hipDevice_t stream_dev = 0;
+    int cur = 0;
+    if (hipStreamGetDevice(stream, &stream_dev) == hipSuccess && hipGetDevice(&cur) == hipSuccess) {
+      if (static_cast<int>(stream_dev) != cur) return KVRA_EINVAL;
+    } else {
+      (void)hipGetLastError();   // could not be asked: go on as before
+    }
+  }
   int cus = 0;
   int64_t slots_owned = kStaticSlots;
   float* scratch_ptr = static_scratch_only ? static_scratch(&cus) : device_scratch(stream, &cus, &slots_owned);
