@@ -32,12 +32,13 @@ WORKLOAD = "llama7b_16k_balanced"
 # A measured constant, not a live reading: `source` names the tracked summary it was copied from and the
 # commit whose kernel that run profiled.
 ATTN_TRAFFIC = {
-    "llama7b_16k_balanced": {"bytes": 4.866e8,
-                             "source": "profiles/chunk_attn_append_llama7b_16k_balanced.md: FETCH_SIZE 408.2 MiB + WRITE_SIZE "
-                                       "55.8 MiB per call (persistent kernel with the merge inside, kernel of commit 0d2a1b4); above the "
-                                       "algorithmic bytes because row tiles of one head and the pieces of a cut unit read the "
-                                       "same K/V at different times (L2 hit rate 64 %); 2 TB/s at this launch time, a "
-                                       "quarter of the HBM peak, so not what bounds the kernel"},
+    "llama7b_16k_balanced": {"bytes": 3.799e8,
+                             "source": "profiles/chunk_attn_append_llama7b_16k_balanced.md: FETCH_SIZE 309.9 MiB + WRITE_SIZE "
+                                       "52.4 MiB per call (persistent kernel, merge inside, tails of chunks 5-7 run in gangs; "
+                                       "kernel of the commit that introduced gang mode); above the algorithmic bytes because "
+                                       "the pieces of cut and leftover units of chunks 0, 1, 3 and 4 read the K/V of their "
+                                       "head at other times than its other row tiles (L2 hit rate 72 %); 1.6 TB/s at this "
+                                       "launch time, a fifth of the HBM peak, so not what bounds the kernel"},
 }
 
 

@@ -138,6 +138,12 @@ int64_t kvra_chunk_attn_noalloc_scratch_bytes(void);
  * `partial_pieces` pieces (over all groups) are not whole units: they leave their un-normalised results in
  * the scratch (`scratch_bytes` = the partial-result slots the launch may touch x 132 KiB), and the piece
  * of a unit that finishes last merges them inside the kernel.
+ *   Gang mode (`gangs` > 0): when a group has fewer units than slots, every unit is cut and at least
+ * `row_tiles` slots have no unit of their own, the tails are not shared out piecemeal: the free slots form
+ * `gangs` gangs of `row_tiles` slots, gang slot r runs the tail of row tile r of `gang_heads` heads one after
+ * the other, and the row tiles of a head then read the same keys at the same time (K/V comes from HBM once,
+ * every cut unit has exactly two pieces); free slots that fit no gang stay idle.  Taken while it ends at most a
+ * tenth later, in tile steps, than the evenly shared plan.
  *   kvra_chunk_attn takes this plan with the CU count of the current device; while it has no scratch (see
  * the conventions at the top) it takes the plan in which no unit is cut.
  * Errors: KVRA_EINVAL (plan NULL, n_cus < 1, sizes as for kvra_chunk_attn), KVRA_EUNSUPPORTED.
@@ -155,6 +161,8 @@ typedef struct kvra_attn_plan {
   int segments;
   int steps_per_slot;
   int partial_pieces;
+  int gangs;            /* gang mode: gangs of row_tiles slots per group that run the tails in step; else 0 */
+  int gang_heads;       /* gang mode: heads (tails) per gang slot */
   int64_t scratch_bytes;
 } kvra_attn_plan;
 int kvra_chunk_attn_plan(int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_kv_heads,

@@ -106,6 +106,8 @@ extern "C" int kvra_chunk_attn_plan(int64_t prefix_len, int64_t chunk_len, int n
   plan->segments = p.segments;
   plan->steps_per_slot = p.steps_per_slot;
   plan->partial_pieces = p.partial_pieces;
+  plan->gangs = p.gangs;
+  plan->gang_heads = p.gang_heads;
   plan->scratch_bytes = kvra::attn_partial_bytes(128) * p.scratch_slots;
   return KVRA_OK;
 }

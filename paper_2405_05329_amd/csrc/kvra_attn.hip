@@ -91,6 +91,8 @@ struct AttnArgs {
   int head_steps;
   int cut;
   int segments;
+  int gangs;         // 0, or (gang mode) the gangs of filler slots per group: see plan_chunk_attn
+  int gang_heads;    // heads each gang slot works through, one tail after the other
   float* scratch;    // partial results: slots_per_group() slots per group; nullptr when nothing is cut
   int* counters;     // key tiles merged so far, one per (group, segment); all zero between launches
 #ifdef KVRA_TRACE
@@ -137,6 +139,23 @@ __host__ __device__ __forceinline__ int unit_steps(const AttnArgs& a, int qt) {
   const int row_hi = (qt + 1) * a.rows_per_wg < rows ? (qt + 1) * a.rows_per_wg : rows;   // exclusive, in virtual rows
   return (a.prefix + (row_hi - 1) / a.G) / a.bn + 1;                                      // key tiles the row tile walks
 }
+
+// Gang mode (a.gangs > 0; every unit of the group is cut, the line of segments is their tails and nothing
+// else): the line is not in unit order but gang by gang, row tile by row tile, head by head, so that the
+// a.gang_heads tails a gang slot takes are consecutive and the slots of a gang - one per row tile - work
+// on the same head at the same time.  Segment s of the line <-> unit j of the group:
+__host__ __device__ __forceinline__ int seg_to_unit(const AttnArgs& a, int s) {
+  if (a.gangs == 0) return s;
+  const int hp = a.Hkv / a.groups, R = a.nq_tiles, k = a.gang_heads;
+  const int g = s / (R * k), rank = (s % (R * k)) / k, i = s % k;
+  return rank * hp + g + a.gangs * i;
+}
+__host__ __device__ __forceinline__ int unit_to_seg(const AttnArgs& a, int j) {
+  if (a.gangs == 0) return j;
+  const int hp = a.Hkv / a.groups, R = a.nq_tiles, k = a.gang_heads;
+  const int head = j % hp, rank = j / hp;
+  return ((head % a.gangs) * R + rank) * k + head / a.gangs;
+}
 // Partial-result slots of a group: id c + s for the piece of segment s that slot c runs (both only grow
 // along the line of segments, so the sum is unique), and slots + segments + s for the head of unit s.
 __host__ __device__ __forceinline__ int slots_per_group(const AttnArgs& a) { return a.slots + 2 * a.segments; }
@@ -167,7 +186,7 @@ struct PieceWalker {
       pc->jt0 = 0;
       const bool is_cut = c < a.cut;
       pc->jt1 = is_cut ? a.head_steps : pc->n;
-      pc->seg = is_cut ? c : -1;
+      pc->seg = is_cut ? unit_to_seg(a, c) : -1;
       pc->slot = is_cut ? P + a.segments + c : -1;
       return true;
     }
@@ -186,7 +205,7 @@ struct PieceWalker {
       round = a.rounds + 1;
       // the unit behind segment `seg` and where the segment starts inside it: the tails of the cut units
       // come first, then the units beyond the complete rounds
-      const int j = seg < a.cut ? seg : a.rounds * P + seg - a.cut;
+      const int j = seg < a.cut ? seg_to_unit(a, seg) : a.rounds * P + seg - a.cut;
       const int first = seg < a.cut ? a.head_steps : 0;
       unit_of(a, x, j, &pc->g, &pc->qt);
       pc->n = unit_steps(a, pc->qt);
@@ -208,7 +227,7 @@ struct PieceWalker {
 // meets this segment.
 template <typename F>
 __host__ __device__ __forceinline__ void for_each_piece_of_segment(const AttnArgs& a, int s, F&& fn) {
-  if (s < a.cut) fn(a.slots + a.segments + s);
+  if (s < a.cut) fn(a.slots + a.segments + seg_to_unit(a, s));
   for (int c = 0; c < a.slots; ++c) {
     const unsigned s0 = a.fill_seg[c], o0 = a.fill_off[c], s1 = a.fill_seg[c + 1], o1 = a.fill_off[c + 1];
     const bool nonempty = s0 < s1 || (s0 == s1 && o0 < o1);
@@ -694,7 +713,7 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, int* last
 #pragma unroll
         for (int e = 0; e < 16; ++e) o[db][e] = fmaf(po[db * 16 + e], wb, o[db][e] * wa);
     };
-    if (pc.seg < a.cut) merge_in(a.slots + a.segments + pc.seg);
+    if (pc.seg < a.cut) merge_in(a.slots + a.segments + seg_to_unit(a, pc.seg));
     static_assert(kMaxSlots <= 256, "four votes of 64 lanes cover the table");
     for (int k = 0; k < 4; ++k) {
       const int c = 64 * k + lane;
@@ -876,6 +895,10 @@ float* static_scratch(int* cus_out) {
 #endif
 constexpr int kPieceAllowance = KVRA_ALLOWANCE;   // what starting and finishing a piece costs, in tile steps
 constexpr int kMinPiece = KVRA_MINPIECE;          // no piece shorter than this many tile steps is cut off a unit
+#ifndef KVRA_GANG_SLACK
+#define KVRA_GANG_SLACK 110
+#endif
+constexpr int kGangSlackPercent = KVRA_GANG_SLACK;   // gang mode may finish this much later (percent of the evenly shared plan); 0 = never
 
 // Shares the line of segments out to the slots so that every slot's load (what it already has plus its
 // share plus one allowance per share) stays within `target`; returns whether the whole line was placed.
@@ -1001,6 +1024,52 @@ int plan_chunk_attn(int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_
   partial += cut;                                             // the heads of the cut units
   plan->partial_pieces = partial * groups;
   plan->scratch_slots = partial > 0 ? (P + 2 * plan->segments) * groups : 0;
+  plan->gangs = 0;
+  plan->gang_heads = 0;
+  // Gang mode.  When the group has fewer units than slots, every unit is cut and at least one row tile's worth
+  // of slots has no unit of its own, the tails can be run in step instead of being handed out piecemeal: the
+  // free slots form gangs of R (one slot per row tile), a gang works through its heads one after the other,
+  // and the R tails of a head then read the same keys at the same time, as the heads of the units do - their
+  // K/V comes from HBM once instead of R times.  Every tail stays whole (two pieces per unit to merge, no
+  // more).  The price is balance: slots that fit no gang stay idle and a gang slot carries whole tails, so the
+  // common finishing time rises by a few steps; the mode is taken while that rise stays within kGangSlack.
+  if (may_cut && plan->rounds == 0 && U == R * hp && P - U >= R) {
+    int ng = std::min((P - U) / R, hp);
+    while (hp % ng != 0) --ng;
+    const int k = hp / ng;
+    auto gang_fits = [&](int64_t target) -> bool {
+      const int64_t head = target - kPieceAllowance;
+      for (int j = 0; j < U; ++j)
+        if (n[j] < head + kMinPiece) return false;      // every unit must be cut, and keep a tail worth a piece
+      if (head < kMinPiece) return false;
+      for (int g = 0; g < ng; ++g)
+        for (int rank = 0; rank < R; ++rank) {
+          int64_t load = 0;
+          for (int i = 0; i < k; ++i) load += n[rank * hp + g + ng * i] - head + kPieceAllowance;
+          if (load > target) return false;
+        }
+      return true;
+    };
+    // loads of gang slots fall as the target (and with it the cut) rises: the smallest target that fits
+    int64_t t = 0;
+    for (int64_t cand = kMinPiece + kPieceAllowance; cand <= n[0] + kPieceAllowance; ++cand)
+      if (gang_fits(cand)) { t = cand; break; }
+    if (t > 0 && t * 100 <= static_cast<int64_t>(plan->steps_per_slot) * kGangSlackPercent) {
+      plan->gangs = ng;
+      plan->gang_heads = k;
+      plan->head_steps = static_cast<int>(t - kPieceAllowance);
+      plan->cut = U;
+      plan->segments = U;
+      plan->steps_per_slot = static_cast<int>(t);
+      for (int c = 0; c <= P; ++c) {
+        const int m = c - U;                               // filler slot number
+        plan->fill_seg[c] = static_cast<unsigned>(m <= 0 ? 0 : std::min(m, ng * R) * k);
+        plan->fill_off[c] = 0;
+      }
+      plan->partial_pieces = 2 * U * groups;
+      plan->scratch_slots = (P + 2 * plan->segments) * groups;
+    }
+  }
   return KVRA_OK;
 }
 
@@ -1032,6 +1101,8 @@ void schedule_args(const AttnPlan& plan, int64_t prefix_len, int64_t chunk_len, 
   a->rounds = plan.rounds;
   a->head_steps = plan.head_steps;
   a->cut = plan.cut;
+  a->gangs = plan.gangs;
+  a->gang_heads = plan.gang_heads;
   a->segments = plan.segments;
   for (int c = 0; c <= plan.slots; ++c) {
     a->fill_seg[c] = plan.fill_seg[c];

@@ -47,6 +47,8 @@ struct AttnPlan {
   int head_steps;      // 0 = no unit is cut
   int cut;             // units 0 .. cut-1 of the first round stop after head_steps key tiles
   int segments;
+  int gangs;           // gang mode: gangs of filler slots per group (0: the line of segments is shared out evenly)
+  int gang_heads;      // gang mode: heads per gang slot
   int steps_per_slot;  // planned tile steps (plus the per-piece allowance) of the busiest slot
   int partial_pieces;  // pieces (all groups) that go through the scratch
   int scratch_slots;   // partial-result slots the launch may touch (all groups)

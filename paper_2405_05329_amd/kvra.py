@@ -37,6 +37,7 @@ class KvraAttnPlan(ctypes.Structure):
                 ("rounds", ctypes.c_int), ("head_steps", ctypes.c_int), ("cut_units", ctypes.c_int),
                 ("segments", ctypes.c_int),
                 ("steps_per_slot", ctypes.c_int), ("partial_pieces", ctypes.c_int),
+                ("gangs", ctypes.c_int), ("gang_heads", ctypes.c_int),
                 ("scratch_bytes", ctypes.c_int64)]
 
 

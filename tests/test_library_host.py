@@ -356,9 +356,42 @@ def test_attention_schedule_of_the_16k_workload():
         assert (p["groups"], p["slots"]) == (8, 32)
         total = sum(pc["jt1"] - pc["jt0"] for pc in pieces)
         ideal = total / 256
-        assert len(per_wg) == 256                                   # no idle compute unit
+        # no idle compute unit, but for the free slots of a group that fit no gang (gang mode, below)
+        idle = 8 * (p["slots"] - p["units"] - p["gangs"] * p["row_tiles"]) if p["gangs"] else 0
+        assert len(per_wg) == 256 - idle and (i >= 5) == (p["gangs"] > 0)
         assert max(per_wg.values()) <= 1.08 * ideal + 3 * PIECE_ALLOWANCE   # allowances included
         assert sorted(per_wg.values())[8] >= 0.9 * ideal               # (the last slot of a group takes what is left)
+
+
+def test_gang_mode_runs_the_tails_of_a_head_in_step():
+    """Chunks 5-7 of the 16k workload: 20 units on the 32 slots of a group, 12 free slots = 2 gangs of 5 (one
+    slot per row tile) + 2 idle.  Every unit is cut once; a gang slot runs the tails of one row tile of two
+    heads, and the five slots of a gang are on the same head at the same position of their lists."""
+    H, d, cus = 32, 128, 256
+    for prefix, c in ((12928, 1280), (14208, 1088), (15296, 1088)):
+        p, pieces, per_wg = _check_schedule(prefix, c, H, H, d, cus)
+        assert (p["gangs"], p["gang_heads"], p["row_tiles"], p["units"], p["cut_units"], p["segments"]) == (2, 2, 5, 20, 20, 20)
+        assert p["partial_pieces"] == 2 * 20 * 8 and len(pieces) == 2 * 20 * 8
+        by_wg = {}
+        for pc in pieces:
+            by_wg.setdefault(pc["workgroup"], []).append(pc)
+        for x in range(8):                                   # group x = workgroup id % 8, slot = id // 8
+            heads = [by_wg[x + 8 * slot] for slot in range(20)]
+            assert all(len(h) == 1 and h[0]["jt0"] == 0 and h[0]["jt1"] == p["head_steps"] for h in heads)
+            for gang in range(2):
+                members = [by_wg[x + 8 * (20 + gang * 5 + r)] for r in range(5)]
+                assert all(len(m) == 2 for m in members)
+                assert sorted(m[0]["row_tile"] for m in members) == [0, 1, 2, 3, 4]
+                for m in members:
+                    assert m[0]["row_tile"] == m[1]["row_tile"] and m[0]["kv_head"] != m[1]["kv_head"]
+                    assert all(t["jt0"] == p["head_steps"] and t["jt1"] == t["unit_steps"] for t in m)
+                for position in range(2):
+                    assert len({m[position]["kv_head"] for m in members}) == 1
+            assert all(x + 8 * slot not in by_wg for slot in (30, 31))
+    # a tenth more tile steps than the evenly shared plan is the limit: chunks 3 and 4 (one gang of 6 for 8
+    # free slots) would end 11 % later and stay as they were
+    for prefix, c in ((10048, 1536), (11584, 1344)):
+        assert kvra.kvra_chunk_attn_plan(prefix, c, H, H, d, cus)["gangs"] == 0
 
 
 def test_attention_schedule_invariants_on_random_shapes():
