@@ -39,7 +39,9 @@
 // length - so that every slot ends up with the same number of tile steps.  A piece that is not a whole unit
 // leaves its un-normalised (O, m, l) in a scratch slot with device-coherent stores and adds its tile steps
 // to the unit's counter; the piece that completes the count merges the unit's partial results in a fixed
-// order (the usual log-sum-exp merge) and writes the rows.  No workgroup waits for another one.
+// order (the usual log-sum-exp merge) and writes the rows.  No workgroup waits for another one.  Where a
+// group's free slots can form gangs of one slot per row tile, the tails of a head are run side by side by a
+// gang instead (gang mode, see plan_chunk_attn), so that they share the K/V stream as the heads do.
 #include "kvra_internal.h"
 
 #include <algorithm>

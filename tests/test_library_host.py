@@ -344,7 +344,7 @@ def _check_schedule(prefix, c, H, Hkv, d, cus):
 
 def test_attention_schedule_of_the_16k_workload():
     """Llama-7B shape, 8 balanced chunks, 256 compute units: 8 groups of 32 slots, and every slot's load (tile
-    steps plus five per piece) within a few steps of the ideal share of its group."""
+    steps plus the allowance per piece) within a few steps of the ideal share of its group."""
     H, d, cus = 32, 128, 256
     bounds = [0, 5824, 8192, 10048, 11584, 12928, 14208, 15296, 16384]
     want = {0: (23, 256, 92, 2, 0), 1: (10, 256, 40, 1, 0), 2: (8, 256, 32, 1, 8), 3: (6, 256, 24, 0, 24),
