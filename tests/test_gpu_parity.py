@@ -352,6 +352,26 @@ def test_cut_unit_launch_shapes(H, Hkv, d, prefix, c):
     print(f"cut units {H}/{Hkv} d{d} prefix {prefix} c {c}: max-abs {mx:.3e} mean-abs {mean:.3e}")
 
 
+@pytest.mark.parametrize("H,Hkv,d,prefix,c,gangs,gang_heads", [(32, 32, 128, 4000, 900, 4, 1), (32, 32, 64, 6000, 1100, 2, 2),
+                                                              (64, 32, 128, 6000, 640, 2, 2)])
+def test_gang_mode_launch_shapes(H, Hkv, d, prefix, c, gangs, gang_heads):
+    """Shapes for which the plan runs the tails of the cut units in gangs (the free slots of a group, one
+    per row tile, work on one head at a time): head_dim 128 and 64, one and two heads per gang slot, grouped
+    queries.  Every row of the chunk is checked."""
+    import torch
+    from paper_2405_05329_amd import kvra
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    plan = kvra.kvra_chunk_attn_plan(prefix, c, H, Hkv, d, cus)
+    if cus == 256:
+        assert (plan["gangs"], plan["gang_heads"]) == (gangs, gang_heads)
+    C = prefix + c
+    q, k, v, scale, res = _run(33, 1, C, H, Hkv, d, [0, prefix, C])
+    rows = list(range(prefix, C))
+    want = orc.attention_rows(_f64(q), _f64(k), _f64(v), rows, scale, rope_base=synth.ROPE_BASE)
+    mx, mean = _check_out(res["out"][rows], want, f"gang mode {H}/{Hkv} d{d} prefix {prefix} c {c}")
+    print(f"gang mode {H}/{Hkv} d{d} prefix {prefix} c {c}: max-abs {mx:.3e} mean-abs {mean:.3e}")
+
+
 def _random_cases(n, seed):
     rng = np.random.default_rng(seed)
     cases = []
