@@ -146,9 +146,12 @@ __host__ __device__ __forceinline__ int unit_steps(const AttnArgs& a, int qt) {
 // else): the line is not in unit order but gang by gang, row tile by row tile, head by head, so that the
 // a.gang_heads tails a gang slot takes are consecutive and the slots of a gang - one per row tile - work
 // on the same head at the same time.  Segment s of the line <-> unit j of the group:
+// (the gangs take the first gangs * gang_heads heads of the group; the tails of the other heads follow in
+// the line head by head, row tile by row tile, for the free slots that fit no gang)
 __host__ __device__ __forceinline__ int seg_to_unit(const AttnArgs& a, int s) {
   if (a.gangs == 0) return s;
-  const int hp = a.Hkv / a.groups, R = a.nq_tiles, k = a.gang_heads;
+  const int hp = a.Hkv / a.groups, R = a.nq_tiles, k = a.gang_heads, gang_segments = a.gangs * R * k;
+  if (s >= gang_segments) return ((s - gang_segments) % R) * hp + a.gangs * k + (s - gang_segments) / R;
   const int g = s / (R * k), rank = (s % (R * k)) / k, i = s % k;
   return rank * hp + g + a.gangs * i;
 }
@@ -156,6 +159,7 @@ __host__ __device__ __forceinline__ int unit_to_seg(const AttnArgs& a, int j) {
   if (a.gangs == 0) return j;
   const int hp = a.Hkv / a.groups, R = a.nq_tiles, k = a.gang_heads;
   const int head = j % hp, rank = j / hp;
+  if (head >= a.gangs * k) return a.gangs * R * k + (head - a.gangs * k) * R + rank;
   return ((head % a.gangs) * R + rank) * k + head / a.gangs;
 }
 // Partial-result slots of a group: id c + s for the piece of segment s that slot c runs (both only grow
@@ -1032,43 +1036,83 @@ int plan_chunk_attn(int64_t prefix_len, int64_t chunk_len, int n_q_heads, int n_
   // of slots has no unit of its own, the tails can be run in step instead of being handed out piecemeal: the
   // free slots form gangs of R (one slot per row tile), a gang works through its heads one after the other,
   // and the R tails of a head then read the same keys at the same time, as the heads of the units do - their
-  // K/V comes from HBM once instead of R times.  Every tail stays whole (two pieces per unit to merge, no
-  // more).  The price is balance: slots that fit no gang stay idle and a gang slot carries whole tails, so the
-  // common finishing time rises by a few steps; the mode is taken while that rise stays within kGangSlack.
+  // K/V comes from HBM once instead of R times - and every such tail stays whole (two pieces per unit to
+  // merge, no more).  Free slots that fit no gang take the tails of the heads the gangs leave over, shared out
+  // evenly among them as before, or stay idle if the gangs take every head.  The price is balance (a gang slot
+  // carries whole tails, idle slots carry nothing): the mode is taken while the common finishing time stays
+  // within kGangSlack of the evenly shared plan's, with the number of gangs and of heads per gang slot that
+  // finish earliest.
   if (may_cut && plan->rounds == 0 && U == R * hp && P - U >= R) {
-    int ng = std::min((P - U) / R, hp);
-    while (hp % ng != 0) --ng;
-    const int k = hp / ng;
-    auto gang_fits = [&](int64_t target) -> bool {
-      const int64_t head = target - kPieceAllowance;
-      for (int j = 0; j < U; ++j)
-        if (n[j] < head + kMinPiece) return false;      // every unit must be cut, and keep a tail worth a piece
-      if (head < kMinPiece) return false;
-      for (int g = 0; g < ng; ++g)
-        for (int rank = 0; rank < R; ++rank) {
-          int64_t load = 0;
-          for (int i = 0; i < k; ++i) load += n[rank * hp + g + ng * i] - head + kPieceAllowance;
-          if (load > target) return false;
+    const int F = P - U;
+    std::vector<int> spare_len;
+    std::vector<int64_t> spare_load;
+    std::vector<unsigned> sp_seg(kMaxSlots + 1), sp_off(kMaxSlots + 1);
+    int spare_partial = 0;
+    // smallest finishing time of ng gangs with k heads per gang slot (0: impossible); leaves the spare slots'
+    // share tables in sp_seg / sp_off
+    auto gang_target = [&](int ng, int k) -> int64_t {
+      const int spare_heads = hp - ng * k, spare_slots = F - ng * R;
+      if (spare_heads < 0 || (spare_heads > 0 && spare_slots < 1)) return 0;
+      for (int64_t target = kMinPiece + kPieceAllowance; target <= n[0] + kPieceAllowance; ++target) {
+        const int64_t head = target - kPieceAllowance;
+        bool ok = head >= kMinPiece;
+        for (int j = 0; ok && j < U; ++j) ok = n[j] >= head + kMinPiece;   // every unit cut, with a tail worth a piece
+        for (int g = 0; ok && g < ng; ++g)
+          for (int rank = 0; ok && rank < R; ++rank) {
+            int64_t load = 0;
+            for (int i = 0; i < k; ++i) load += n[rank * hp + g + ng * i] - head + kPieceAllowance;
+            ok = load <= target;
+          }
+        if (ok && spare_heads > 0) {
+          spare_len.clear();
+          for (int h = ng * k; h < hp; ++h)
+            for (int rank = 0; rank < R; ++rank) spare_len.push_back(n[rank * hp + h] - static_cast<int>(head));
+          spare_load.assign(spare_slots, 0);
+          ok = share_out(spare_len, spare_load, target, false, static_cast<int>(spare_len.size()), sp_seg.data(),
+                         sp_off.data(), &spare_partial);
         }
-      return true;
+        if (ok) return target;
+      }
+      return 0;
     };
-    // loads of gang slots fall as the target (and with it the cut) rises: the smallest target that fits
-    int64_t t = 0;
-    for (int64_t cand = kMinPiece + kPieceAllowance; cand <= n[0] + kPieceAllowance; ++cand)
-      if (gang_fits(cand)) { t = cand; break; }
-    if (t > 0 && t * 100 <= static_cast<int64_t>(plan->steps_per_slot) * kGangSlackPercent) {
+    int best_ng = 0, best_k = 0;
+    int64_t best_t = 0;
+    for (int ng = std::min(F / R, hp); ng >= 1; --ng)
+      for (int k = 1; ng * k <= hp; ++k) {
+        const int64_t t = gang_target(ng, k);
+        if (t > 0 && (best_t == 0 || t < best_t || (t == best_t && ng * k > best_ng * best_k))) {
+          best_t = t;
+          best_ng = ng;
+          best_k = k;
+        }
+      }
+    if (best_t > 0 && best_t * 100 <= static_cast<int64_t>(plan->steps_per_slot) * kGangSlackPercent) {
+      const int ng = best_ng, k = best_k, gang_segments = ng * R * k, spare_slots = F - ng * R;
+      spare_partial = 0;
+      (void)gang_target(ng, k);                              // (fills the spare slots' tables again)
       plan->gangs = ng;
       plan->gang_heads = k;
-      plan->head_steps = static_cast<int>(t - kPieceAllowance);
+      plan->head_steps = static_cast<int>(best_t - kPieceAllowance);
       plan->cut = U;
       plan->segments = U;
-      plan->steps_per_slot = static_cast<int>(t);
+      plan->steps_per_slot = static_cast<int>(best_t);
       for (int c = 0; c <= P; ++c) {
-        const int m = c - U;                               // filler slot number
-        plan->fill_seg[c] = static_cast<unsigned>(m <= 0 ? 0 : std::min(m, ng * R) * k);
-        plan->fill_off[c] = 0;
+        const int m = c - U;                                 // filler slot number: gang slots first, then spare ones
+        if (m <= 0) {
+          plan->fill_seg[c] = 0;
+          plan->fill_off[c] = 0;
+        } else if (m <= ng * R) {
+          plan->fill_seg[c] = static_cast<unsigned>(m * k);
+          plan->fill_off[c] = 0;
+        } else if (ng * k < hp) {
+          plan->fill_seg[c] = static_cast<unsigned>(gang_segments) + sp_seg[std::min(m - ng * R, spare_slots)];
+          plan->fill_off[c] = sp_off[std::min(m - ng * R, spare_slots)];
+        } else {
+          plan->fill_seg[c] = static_cast<unsigned>(U);
+          plan->fill_off[c] = 0;
+        }
       }
-      plan->partial_pieces = 2 * U * groups;
+      plan->partial_pieces = (U + gang_segments + (ng * k < hp ? spare_partial : 0)) * groups;
       plan->scratch_slots = (P + 2 * plan->segments) * groups;
     }
   }

@@ -357,10 +357,12 @@ def test_attention_schedule_of_the_16k_workload():
         total = sum(pc["jt1"] - pc["jt0"] for pc in pieces)
         ideal = total / 256
         # no idle compute unit, but for the free slots of a group that fit no gang (gang mode, below)
-        idle = 8 * (p["slots"] - p["units"] - p["gangs"] * p["row_tiles"]) if p["gangs"] else 0
-        assert len(per_wg) == 256 - idle and (i >= 5) == (p["gangs"] > 0)
+        heads_left = 4 - p["gangs"] * p["gang_heads"]           # heads whose tails go to the free slots outside the gangs
+        idle = 8 * (p["slots"] - p["units"] - p["gangs"] * p["row_tiles"]) if p["gangs"] and heads_left == 0 else 0
+        assert len(per_wg) == 256 - idle and (i >= 3) == (p["gangs"] > 0)
         assert max(per_wg.values()) <= 1.08 * ideal + 3 * PIECE_ALLOWANCE   # allowances included
-        assert sorted(per_wg.values())[8] >= 0.9 * ideal               # (the last slot of a group takes what is left)
+        if not p["gangs"]:                                           # (a gang slot carries whole tails, short ones too)
+            assert sorted(per_wg.values())[8] >= 0.9 * ideal           # (the last slot of a group takes what is left)
 
 
 def test_gang_mode_runs_the_tails_of_a_head_in_step():
@@ -388,10 +390,24 @@ def test_gang_mode_runs_the_tails_of_a_head_in_step():
                 for position in range(2):
                     assert len({m[position]["kv_head"] for m in members}) == 1
             assert all(x + 8 * slot not in by_wg for slot in (30, 31))
-    # a tenth more tile steps than the evenly shared plan is the limit: chunks 3 and 4 (one gang of 6 for 8
-    # free slots) would end 11 % later and stay as they were
+    # chunks 3 and 4: 24 units, 8 free slots for 6 row tiles: one gang runs three heads, the two free slots
+    # left over share the six tails of the fourth head (three whole tails each), nobody idles
     for prefix, c in ((10048, 1536), (11584, 1344)):
-        assert kvra.kvra_chunk_attn_plan(prefix, c, H, H, d, cus)["gangs"] == 0
+        p, pieces, per_wg = _check_schedule(prefix, c, H, H, d, cus)
+        assert (p["gangs"], p["gang_heads"], p["row_tiles"], p["units"], p["cut_units"]) == (1, 3, 6, 24, 24)
+        assert len(per_wg) == 256 and p["partial_pieces"] == 2 * 24 * 8
+        by_wg = {}
+        for pc in pieces:
+            by_wg.setdefault(pc["workgroup"], []).append(pc)
+        for x in range(8):
+            members = [by_wg[x + 8 * (24 + r)] for r in range(6)]
+            assert all(len(m) == 3 and len({t["row_tile"] for t in m}) == 1 for m in members)
+            for position in range(3):
+                assert len({m[position]["kv_head"] for m in members}) == 1
+            spare = [by_wg[x + 8 * 30], by_wg[x + 8 * 31]]
+            assert all(len(m) == 3 and len({t["kv_head"] for t in m}) == 1 for m in spare)
+            assert spare[0][0]["kv_head"] == spare[1][0]["kv_head"] not in {t["kv_head"] for m in members for t in m}
+            assert sorted(t["row_tile"] for m in spare for t in m) == [0, 1, 2, 3, 4, 5]
 
 
 def test_attention_schedule_invariants_on_random_shapes():
