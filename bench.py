@@ -32,13 +32,14 @@ WORKLOAD = "llama7b_16k_balanced"
 # A measured constant, not a live reading: `source` names the tracked summary it was copied from and the
 # commit whose kernel that run profiled.
 ATTN_TRAFFIC = {
-    "llama7b_16k_balanced": {"bytes": 3.799e8,
-                             "source": "profiles/chunk_attn_append_llama7b_16k_balanced.md: FETCH_SIZE 309.9 MiB + WRITE_SIZE "
-                                       "52.4 MiB per call (persistent kernel, merge inside, tails of chunks 5-7 run in gangs; "
-                                       "kernel of the commit that introduced gang mode); above the algorithmic bytes because "
-                                       "the pieces of cut and leftover units of chunks 0, 1, 3 and 4 read the K/V of their "
-                                       "head at other times than its other row tiles (L2 hit rate 72 %); 1.6 TB/s at this "
-                                       "launch time, a fifth of the HBM peak, so not what bounds the kernel"},
+    "llama7b_16k_balanced": {"bytes": 3.484e8,
+                             "source": "profiles/chunk_attn_append_llama7b_16k_balanced.md: FETCH_SIZE 281.0 MiB + WRITE_SIZE "
+                                       "51.3 MiB per call (persistent kernel, merge inside, tails of chunks 3-7 run in gangs; "
+                                       "kernel of the commit that generalised gang mode); above the algorithmic bytes because "
+                                       "the pieces of the leftover units of chunks 0 and 1, and a fourth of the tails of chunks "
+                                       "3 and 4, read the K/V of their head at other times than its other row tiles (L2 hit "
+                                       "rate 74 %); 1.5 TB/s at this launch time, a fifth of the HBM peak, so not what bounds "
+                                       "the kernel"},
 }
 
 

@@ -142,8 +142,9 @@ int64_t kvra_chunk_attn_noalloc_scratch_bytes(void);
  * `row_tiles` slots have no unit of their own, the tails are not shared out piecemeal: the free slots form
  * `gangs` gangs of `row_tiles` slots, gang slot r runs the tail of row tile r of `gang_heads` heads one after
  * the other, and the row tiles of a head then read the same keys at the same time (K/V comes from HBM once,
- * every cut unit has exactly two pieces); free slots that fit no gang stay idle.  Taken while it ends at most a
- * tenth later, in tile steps, than the evenly shared plan.
+ * every such unit has exactly two pieces); the gangs take the first gangs * gang_heads heads of the group, and
+ * free slots that fit no gang share the tails of the other heads as above, or stay idle if there is none.  Taken
+ * while it ends at most a tenth later, in tile steps, than the evenly shared plan.
  *   kvra_chunk_attn takes this plan with the CU count of the current device; while it has no scratch (see
  * the conventions at the top) it takes the plan in which no unit is cut.
  * Errors: KVRA_EINVAL (plan NULL, n_cus < 1, sizes as for kvra_chunk_attn), KVRA_EUNSUPPORTED.
