@@ -697,7 +697,13 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, int* last
     // slots whose share of the line of segments meets it), merged one after the other into (O, m, l)
     // starting from nothing: the result does not depend on which piece happened to be the last.
     // Which slots: every lane tests four slots of the table, the wave votes.
+    // This piece's own partial result is not read back: what it stored is what its registers hold, so taking
+    // it from there when its turn in the order comes gives the same bits and saves one of the unit's reads.
     const float* mine = group_slots + wave * WAVE_FLOATS + lane;
+    f32x16 own_o[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db) own_o[db] = o[db];
+    const float own_m = m, own_l = l;
     m = kNoKeyYet;
     l = 0.0f;
 #pragma unroll
@@ -707,9 +713,18 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, int* last
     auto merge_in = [&](int slot) {
       const float* p = mine + static_cast<long long>(slot) * kPartialFloats(D);
       float po[DB * 16];
+      float pm, pl;
+      if (slot == pc.slot) {
 #pragma unroll
-      for (int i = 0; i < DB * 16; ++i) po[i] = load_coherent(p + i * 64);
-      const float pm = load_coherent(p + (DB * 16) * 64), pl = load_coherent(p + (DB * 16 + 1) * 64);
+        for (int i = 0; i < DB * 16; ++i) po[i] = own_o[i / 16][i % 16];
+        pm = own_m;
+        pl = own_l;
+      } else {
+#pragma unroll
+        for (int i = 0; i < DB * 16; ++i) po[i] = load_coherent(p + i * 64);
+        pm = load_coherent(p + (DB * 16) * 64);
+        pl = load_coherent(p + (DB * 16 + 1) * 64);
+      }
       const float mn = fmaxf(m, pm);
       const float wa = __builtin_amdgcn_exp2f(m - mn), wb = __builtin_amdgcn_exp2f(pm - mn);
       m = mn;
