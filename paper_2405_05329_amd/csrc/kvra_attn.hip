@@ -672,7 +672,22 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, int* last
     // added to its counter; the piece that completes the count reads the others with device-coherent loads.
     constexpr int WAVE_FLOATS = (DB * 16 + 2) * 64;
     float* group_slots = a.scratch + static_cast<long long>(x) * slots_per_group(a) * kPartialFloats(D);
-    {
+    int* counter = a.counters + x * kMaxSlots + pc.seg;
+    // The piece that ends a unit's keys usually starts after the others have finished (it is the one the
+    // schedule places last).  It looks at the counter first: if every other piece has already been counted,
+    // it is the one that merges, nobody will read its partial result, and the store and its wait are left
+    // out.  (The others' results are visible then: each was acknowledged before its count was added.)
+    bool all_others_counted = false;
+    if (pc.jt0 > 0 && pc.jt1 == pc.n) {
+      if (tid == 0) {
+        const int seen = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *last_flag = (seen + nt == pc.n) ? 1 : 0;
+      }
+      __syncthreads();
+      all_others_counted = *last_flag != 0;
+      __syncthreads();                     // the flag is written again below
+    }
+    if (!all_others_counted) {
       float* p = group_slots + static_cast<long long>(pc.slot) * kPartialFloats(D) + wave * WAVE_FLOATS + lane;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
@@ -680,18 +695,17 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, int* last
         for (int e = 0; e < 16; ++e) store_coherent(p + (db * 16 + e) * 64, o[db][e]);
       store_coherent(p + (DB * 16) * 64, m);
       store_coherent(p + (DB * 16 + 1) * 64, l);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+      if (tid == 0) {
+        const int before = atomicAdd(counter, nt);
+        *last_flag = (before + nt == pc.n) ? 1 : 0;
+      }
+      __syncthreads();
+      const bool last = *last_flag != 0;
+      __syncthreads();                     // the flag may be rewritten by the next piece
+      if (!last) return;
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    int* counter = a.counters + x * kMaxSlots + pc.seg;
-    if (tid == 0) {
-      const int before = atomicAdd(counter, nt);
-      *last_flag = (before + nt == pc.n) ? 1 : 0;
-    }
-    __syncthreads();
-    const bool last = *last_flag != 0;
-    __syncthreads();                       // the flag may be rewritten by the next piece
-    if (!last) return;
     if (tid == 0) *counter = 0;            // ready for the next launch
     // The unit's pieces in their fixed order (the head if the segment is the tail of a cut unit, then the
     // slots whose share of the line of segments meets it), merged one after the other into (O, m, l)
