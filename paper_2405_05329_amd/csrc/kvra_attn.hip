@@ -673,12 +673,12 @@ __device__ __forceinline__ void attend(const AttnArgs& a, u32x4* smem, int* last
     constexpr int WAVE_FLOATS = (DB * 16 + 2) * 64;
     float* group_slots = a.scratch + static_cast<long long>(x) * slots_per_group(a) * kPartialFloats(D);
     int* counter = a.counters + x * kMaxSlots + pc.seg;
-    // The piece that ends a unit's keys usually starts after the others have finished (it is the one the
-    // schedule places last).  It looks at the counter first: if every other piece has already been counted,
-    // it is the one that merges, nobody will read its partial result, and the store and its wait are left
-    // out.  (The others' results are visible then: each was acknowledged before its count was added.)
+    // A piece looks at the unit's counter first: if every other piece has already been counted, it is the
+    // one that merges, nobody will read its partial result, and the store and the wait for it are left out
+    // (in a unit of two pieces, whichever comes second).  The others' results are visible then: each was
+    // acknowledged before its count was added.  A look that comes too early only costs the round trip.
     bool all_others_counted = false;
-    if (pc.jt0 > 0 && pc.jt1 == pc.n) {
+    {
       if (tid == 0) {
         const int seen = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         *last_flag = (seen + nt == pc.n) ? 1 : 0;
