@@ -285,6 +285,8 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--event-every", type=int, default=4,
+                    help="every how many timed steps carry the HIP events that time the kernels (1 = every step)")
     ap.add_argument("--no-makespan", action="store_true",
                     help="skip the equal-split and kvra_balance makespan measurements (profiling runs)")
     ap.add_argument("--no-extras", action="store_true", help="same as --no-makespan (kept for older command lines)")
@@ -382,20 +384,27 @@ def main():
     for s in range(args.warmup, args.warmup + args.steps):   # restore un-rotated Q where a buffer is reused
         if s >= n_buf:
             q_work[s % n_buf].copy_(q_master)
-    ev = [new_events(p) for _ in range(args.steps)]
-    first_ev = torch.cuda.Event(enable_timing=True)
+    # Every event costs stream time that is no part of the workload (2 p + 1 events per step would be 2-3 % of it),
+    # so only every args.event_every-th timed step carries them: one before its first append, two per chunk.
+    every = max(1, args.event_every)
+    ev = {s: (torch.cuda.Event(enable_timing=True), new_events(p)) for s in range(0, args.steps, every)}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    first_ev.record(stream)
     for s in range(args.steps):
-        run_step(bounds, q_work[(args.warmup + s) % n_buf], ev[s])
+        if s in ev:
+            ev[s][0].record(stream)
+            run_step(bounds, q_work[(args.warmup + s) % n_buf], ev[s][1])
+        else:
+            run_step(bounds, q_work[(args.warmup + s) % n_buf])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
     ms_per_step = wall * 1e3 / args.steps
     flops_chunk = [useful_flops(bounds[i], bounds[i + 1] - bounds[i], H, d) for i in range(p)]
     flops_step = sum(flops_chunk)
-    append_ms, attn_ms = chunk_times(first_ev, ev)   # [steps, p]
+    per_step = [chunk_times(first, [pairs]) for first, pairs in ev.values()]
+    append_ms = np.concatenate([a for a, _ in per_step])   # [steps with events, p]
+    attn_ms = np.concatenate([t for _, t in per_step])
     attn_mean = attn_ms.mean(axis=0)
     append_mean = append_ms.mean(axis=0)
     attn_avg_launch_ms = float(attn_ms.mean())
@@ -423,8 +432,9 @@ def main():
                      "algorithmic_bytes": algorithmic_bytes,
                      "traffic_over_algorithmic": traffic["bytes"] / algorithmic_bytes if traffic else None,
                      "avg_launch_ms": attn_avg_launch_ms,
-                     "timing": "HIP events on the launch stream around every kvra_chunk_attn call of the timed steps; the append "
-                               "is timed from the previous call's end event to this call's start event"},
+                     "timing": f"HIP events on the launch stream around every kvra_chunk_attn call of every "
+                               f"{every}. timed step ({len(ev)} of {args.steps} steps, {len(ev) * p} launches); the append "
+                               "is timed from the previous event to the call's start event"},
         "per_chunk": {"attn_ms": [round(float(x), 4) for x in attn_mean],
                       "attn_ms_median": [round(float(x), 4) for x in np.median(attn_ms, axis=0)],
                       "attn_ms_min": [round(float(x), 4) for x in attn_ms.min(axis=0)],
@@ -436,6 +446,21 @@ def main():
         "paper_context": "KV-Runahead reports 1.4x (Llama 7B) / 1.6x (Falcon 7B) TTFT speedup over tensor/sequence "
                          "parallelism on 8x A100, FP16, 300 GB/s (whole model; not comparable to this kernel metric)",
     }
+
+    # What the matrix pipes of THIS GPU sustain with nothing else in the way (a loop of MFMAs on register operands
+    # of the workload's value distribution, all compute units busy, right after the timed steps): GPUs of one model
+    # differ by several per cent in the clock they hold under that load, and the attention kernel follows it.
+    try:
+        from paper_2405_05329_amd import probe
+        alone = probe.matrix_pipes_alone(torch)
+        alone["achieved_over_it"] = achieved / alone["tflops"]
+        alone["what"] = ("v_mfma_f32_32x32x16_bf16 back to back on register operands, no memory or LDS access in the "
+                         "loop, measured in this process after the timed steps; context for frac, which stays "
+                         "against the published peak")
+        result["roofline"]["matrix_pipes_alone"] = alone
+    except (RuntimeError, OSError) as e:
+        result["roofline"]["matrix_pipes_alone"] = None
+        print(f"bench.py: matrix-pipe probe skipped: {e}", file=sys.stderr)
 
     reps = 5
 

@@ -117,7 +117,22 @@ __global__ __launch_bounds__(512, 1) void probe_valu_kernel(const bf16x8* operan
   sink[static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x] = r;
 }
 
+// One wave that writes the 100 MHz clock: put before and after another kernel on the same stream, it tells how
+// long the stream takes to get from one kernel into the next.
+__global__ void probe_stamp_kernel(unsigned long long* out) {
+  const unsigned long long t = wall_clock64();
+  if (threadIdx.x == 0) out[0] = t;
+}
+
 }  // namespace
+
+// out: device, one 64-bit word, receives the 100 MHz clock read by a one-wave kernel launched on `stream`.
+extern "C" int kvra_probe_stamp(void* out, void* stream) {
+  if (out == nullptr) return -1;
+  hipLaunchKernelGGL(probe_stamp_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream),
+                     static_cast<unsigned long long*>(out));
+  return static_cast<int>(hipGetLastError());
+}
 
 // operands: device, 8 x 64 x 16 bytes (4 A and 4 B fragments per lane, bf16); sink: device,
 // workgroups * 64 * waves floats; stamps: device, 4 * workgroups * waves 64-bit words (XCD, start, end, shader-clock cycles per wave),

@@ -22,6 +22,38 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
+def matrix_pipes_alone(torch, iters=20000, reps=3):
+    """TFLOP/s of the MFMA-only loop on this GPU right now: all compute units busy, two waves per SIMD, N(0,1)
+    bf16 operands (the value distribution of the synthetic workloads).  Median of `reps` launches after one
+    untimed launch.  Raises if the probe library has not been built."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libkvra_probe.so")
+    if not os.path.exists(path):
+        raise RuntimeError("libkvra_probe.so is not built: python -m paper_2405_05329_amd.build --probe")
+    lib = ctypes.CDLL(path)
+    vp, i32 = ctypes.c_void_p, ctypes.c_int
+    lib.kvra_probe_mfma.restype = i32
+    lib.kvra_probe_mfma.argtypes = [vp, vp, i32, i32, i32, vp, vp]
+    cus = torch.cuda.get_device_properties(torch.cuda.current_device()).multi_processor_count
+    g = torch.Generator(device="cuda")
+    g.manual_seed(0)
+    ops = torch.randn((8, 64, 8), device="cuda", generator=g).to(torch.bfloat16)
+    sink = torch.empty(cus * 512, dtype=torch.float32, device="cuda")
+    times = []
+    for rep in range(reps + 1):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        rc = lib.kvra_probe_mfma(ops.data_ptr(), sink.data_ptr(), cus, 8, iters, None, None)
+        if rc != 0:
+            raise RuntimeError(f"kvra_probe_mfma returned {rc}")
+        e1.record()
+        torch.cuda.synchronize()
+        if rep:
+            times.append(e0.elapsed_time(e1))
+    ms = float(np.median(times))
+    return {"tflops": cus * 8 * iters * 16 * 32768.0 / (ms * 1e-3) / 1e12, "ms": ms, "busy_cus": cus,
+            "waves_per_simd": 2, "operands": "N(0,1) bf16"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--iters", type=int, default=20000)

@@ -25,6 +25,11 @@ tile step done and its end, together with the compute unit it ran on.  For every
              over the workgroups; it lies before `span` begins, so it is part of launch - span
   launch - span   what the event pair sees beyond the workgroups' own time (dispatch, completion); the stamps
              come from the timeline build, which runs a little slower, so this can come out negative
+  before, after   the same launch's dispatch and completion measured directly: a one-wave kernel that reads the
+             same clock sits before and after the stamped attention launch on the stream (probe library);
+             before = its stamp to the first workgroup's first stamp, after = last workgroup exit to the
+             second kernel's stamp; `empty` = stamp to stamp of two such kernels with nothing in between
+             (what any kernel boundary on the stream costs).  Blank without the probe library.
 
 Per CU, span = ramp + pro + steps + epi + gap + tail; the columns are these terms averaged over the CUs
 (a CU that never got a workgroup counts as ramp = span).
@@ -70,6 +75,12 @@ def main():
     tlib.kvra_trace_attach.restype = i32
     tlib.kvra_trace_attach.argtypes = [vp, ctypes.c_longlong]
 
+    probe_path = os.path.join(pkg, "libkvra_probe.so")
+    plib = ctypes.CDLL(probe_path) if os.path.exists(probe_path) else None
+    if plib is not None:
+        plib.kvra_probe_stamp.restype = i32
+        plib.kvra_probe_stamp.argtypes = [vp, vp]
+
     torch.cuda.set_device(0)
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     cfg = synth.CONFIGS[args.workload]
@@ -87,6 +98,7 @@ def main():
     kvra.kvra_append_kv(k_in, v_in, q, k_cache, v_cache, 0, C, C, H, Hkv, d, synth.ROPE_BASE)
     max_groups = 1 << 12
     trace = torch.zeros((max_groups * TRACE_PIECES, TRACE_WORDS), dtype=torch.int64, device="cuda")
+    marks = torch.zeros(3, dtype=torch.int64, device="cuda")
     torch.cuda.synchronize()
 
     # launch time: product library, HIP events around every attention call inside whole steps of the workload
@@ -128,19 +140,28 @@ def main():
                     assert rc == 0, rc
                     stamped = step == 1 and w == i
                     if stamped:
+                        if plib is not None:
+                            plib.kvra_probe_stamp(marks.data_ptr(), None)
                         tlib.kvra_trace_attach(trace.data_ptr(), max_groups)
                     rc = tlib.kvra_chunk_attn(q[sl].data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), wlo, wc, H, Hkv, d,
                                               scale, out[sl].data_ptr(), None)
                     assert rc == 0, rc
                     if stamped:
                         tlib.kvra_trace_attach(None, 0)
+                        if plib is not None:
+                            plib.kvra_probe_stamp(marks[1:].data_ptr(), None)
+                            plib.kvra_probe_stamp(marks[2:].data_ptr(), None)
             torch.cuda.synchronize()
             n_groups = plan["groups"] * plan["slots"]
             t = trace[:n_groups * TRACE_PIECES].cpu().numpy().astype(np.uint64)
             t = t[t[:, 3] != 0]                       # one record per piece a workgroup ran
-            spans.append((int(t[:, 3].max() - t[:, 0].min()), t))
+            mk = marks.cpu().numpy().astype(np.int64)
+            around = ((int(t[:, 0].min()) - int(mk[0])) * TICK_US, (int(mk[1]) - int(t[:, 3].max())) * TICK_US,
+                      (int(mk[2]) - int(mk[1])) * TICK_US) if plib is not None else None
+            spans.append((int(t[:, 3].max() - t[:, 0].min()), t, around))
         spans.sort(key=lambda x: x[0])
         t = spans[len(spans) // 2][1]
+        around = tuple(float(np.median([s[2][j] for s in spans])) for j in range(3)) if plib is not None else None
         dumps[f"chunk{i}"] = t
         t0 = t[:, 0].min()
         enter, loop0, loop1, exit_ = [(t[:, j] - t0).astype(np.float64) * TICK_US for j in range(4)]
@@ -168,7 +189,7 @@ def main():
         rows.append(dict(chunk=i, prefix=lo, c=c, groups=len(steps), plan=plan, launch=launch_us, span=span,
                          total_steps=float(steps.sum()), in_steps=in_steps, pro=pro, epi=epi, gap=gap / n_cu,
                          ramp=(ramp + idle_cus * span) / n_cu, tail=tail / n_cu, idle_cus=idle_cus,
-                         step_med=float(np.median(per_step)), cus_used=len(keys), ghz=ghz,
+                         step_med=float(np.median(per_step)), cus_used=len(keys), ghz=ghz, around=around,
                          entry=float(entry_to_start[entry_to_start > 0].mean()) if (entry_to_start > 0).any() else 0.0))
     flops = lambda lo, c: 4 * d * H * (c * lo + c * (c + 1) // 2)
     print(f"workload {args.workload}: {H}/{Hkv} heads x {d}, context {C}; device with {cus} CUs; times in us")
@@ -176,8 +197,9 @@ def main():
           f"{rows[0]['plan']['key_tile']} keys x {rows[0]['plan']['rows_per_tile']} rows; "
           "2048 matrix-pipe cycles per SIMD at head_dim 128 and 64 alike")
     print()
-    print("| chunk | prefix | c | units, pieces | row tile | launch | TFLOP/s | span | ideal | steps | pro | epi | gap | ramp | tail | launch - span | entry | step med | GHz | cycles per step |")
-    print("|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|")
+    print("| chunk | prefix | c | units, pieces | row tile | launch | TFLOP/s | span | ideal | steps | pro | epi | gap | ramp | tail | launch - span | before | after | empty | entry | step med | GHz | cycles per step |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|")
+    around_txt = lambda a: " | ".join(f"{x:.1f}" for x in a) if a is not None else " | | "
     for r in rows:
         p = r["plan"]
         shape = f"{p['units'] * p['groups']} u, {r['groups']} p" + (f", {p['partial_pieces']} merged" if p["partial_pieces"] else "")
@@ -185,7 +207,7 @@ def main():
         print(f"| {r['chunk']} | {r['prefix']} | {r['c']} | {shape} | {p['rows_per_tile']} | {r['launch']:.1f} | "
               f"{flops(r['prefix'], r['c']) / r['launch'] / 1e6:.0f} | {r['span']:.1f} | {ideal:.1f} | {r['in_steps']:.1f} | "
               f"{r['pro']:.1f} | {r['epi']:.1f} | {r['gap']:.1f} | {r['ramp']:.1f} | {r['tail']:.1f} | "
-              f"{r['launch'] - r['span']:.1f} | {r['entry']:.1f} | {r['step_med']:.3f} | {r['ghz']:.2f} | {r['step_med'] * r['ghz'] * 1e3:.0f} |")
+              f"{r['launch'] - r['span']:.1f} | {around_txt(r['around'])} | {r['entry']:.1f} | {r['step_med']:.3f} | {r['ghz']:.2f} | {r['step_med'] * r['ghz'] * 1e3:.0f} |")
     tot_launch = sum(r["launch"] for r in rows)
     tot_ideal = sum(r["total_steps"] / cus * r["step_med"] for r in rows)
     print()
