@@ -372,6 +372,34 @@ def test_gang_mode_launch_shapes(H, Hkv, d, prefix, c, gangs, gang_heads):
     print(f"gang mode {H}/{Hkv} d{d} prefix {prefix} c {c}: max-abs {mx:.3e} mean-abs {mean:.3e}")
 
 
+@pytest.mark.parametrize("H,Hkv,d,prefix,c", [(32, 32, 128, 4000, 900), (32, 32, 128, 5824, 2368), (71, 1, 64, 5824, 1280),
+                                               (32, 8, 128, 3000, 1280)])
+def test_repeated_launches_give_the_same_bits(H, Hkv, d, prefix, c):
+    """Which piece of a cut unit arrives last, and so merges, differs from launch to launch; the merge runs in
+    a fixed order whoever does it, so the output bits must not: the same call eight times, other work on the
+    stream in between, every output equal to the first bit for bit (gang mode, leftover units of a second
+    round, one shared K/V head, grouped queries)."""
+    import torch
+    from gpu_pipeline import to_dev
+    from paper_2405_05329_amd import kvra
+    C = prefix + c
+    q, k, v = synth.make_qkv(3, 34, C, H, Hkv, d)
+    dq, kc, vc = to_dev(q[prefix:]), to_dev(k), to_dev(v)
+    scale = synth.default_scale(d)
+    outs = []
+    filler = torch.empty(1 << 22, dtype=torch.float32, device="cuda")
+    for rep in range(8):
+        out = torch.zeros((c, H, d), dtype=torch.bfloat16, device="cuda")
+        kvra.kvra_chunk_attn(dq, kc, vc, prefix, c, H, Hkv, d, scale, out)
+        if rep % 2:
+            filler.normal_()          # the next launch starts with the chip in another state
+        outs.append(out)
+    torch.cuda.synchronize()
+    assert torch.isfinite(outs[0].float()).all()
+    for rep in range(1, 8):
+        assert torch.equal(outs[rep].view(torch.int16), outs[0].view(torch.int16)), f"launch {rep} differs from launch 0"
+
+
 def _random_cases(n, seed):
     rng = np.random.default_rng(seed)
     cases = []
