@@ -32,14 +32,14 @@ WORKLOAD = "llama7b_16k_balanced"
 # A measured constant, not a live reading: `source` names the tracked summary it was copied from and the
 # commit whose kernel that run profiled.
 ATTN_TRAFFIC = {
-    "llama7b_16k_balanced": {"bytes": 3.484e8,
-                             "source": "profiles/chunk_attn_append_llama7b_16k_balanced.md: FETCH_SIZE 281.0 MiB + WRITE_SIZE "
-                                       "51.3 MiB per call (persistent kernel, merge inside, tails of chunks 3-7 run in gangs; "
-                                       "kernel of the commit that generalised gang mode); above the algorithmic bytes because "
-                                       "the pieces of the leftover units of chunks 0 and 1, and a fourth of the tails of chunks "
-                                       "3 and 4, read the K/V of their head at other times than its other row tiles (L2 hit "
-                                       "rate 74 %); 1.5 TB/s at this launch time, a fifth of the HBM peak, so not what bounds "
-                                       "the kernel"},
+    "llama7b_16k_balanced": {"bytes": 3.18e8,
+                             "source": "profiles/chunk_attn_append_llama7b_16k_balanced.md: FETCH_SIZE 265.8 MiB + WRITE_SIZE "
+                                       "37.4 MiB per call (persistent kernel, merge inside, tails of chunks 3-7 run in gangs, "
+                                       "the merging piece of a cut unit stores no partial result of its own); above the "
+                                       "algorithmic bytes because the pieces of the leftover units of chunks 0 and 1, and a "
+                                       "fourth of the tails of chunks 3 and 4, read the K/V of their head at other times than "
+                                       "its other row tiles (L2 hit rate 76 %); 1.3 TB/s at this launch time, a sixth of the "
+                                       "HBM peak, so not what bounds the kernel"},
 }
 
 
@@ -288,7 +288,8 @@ def main():
     ap.add_argument("--event-every", type=int, default=4,
                     help="every how many timed steps carry the HIP events that time the kernels (1 = every step)")
     ap.add_argument("--no-makespan", action="store_true",
-                    help="skip the equal-split and kvra_balance makespan measurements (profiling runs)")
+                    help="skip the equal-split and kvra_balance makespan measurements and the matrix-pipe probe "
+                         "(profiling runs: only the workload's own kernels are launched)")
     ap.add_argument("--no-extras", action="store_true", help="same as --no-makespan (kept for older command lines)")
     ap.add_argument("--extras", action="store_true",
                     help="also: HIP-graph replay of the step, the chain-of-processes TTFT, the paper's grid search "
@@ -451,6 +452,8 @@ def main():
     # of the workload's value distribution, all compute units busy, right after the timed steps): GPUs of one model
     # differ by several per cent in the clock they hold under that load, and the attention kernel follows it.
     try:
+        if args.no_makespan or args.no_extras:
+            raise RuntimeError("left out of profiling runs (--no-makespan)")
         from paper_2405_05329_amd import probe
         alone = probe.matrix_pipes_alone(torch)
         alone["achieved_over_it"] = achieved / alone["tflops"]
