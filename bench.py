@@ -388,7 +388,8 @@ def main():
     # Every event costs stream time that is no part of the workload (2 p + 1 events per step would be 2-3 % of it),
     # so only every args.event_every-th timed step carries them: one before its first append, two per chunk.
     every = max(1, args.event_every)
-    ev = {s: (torch.cuda.Event(enable_timing=True), new_events(p)) for s in range(0, args.steps, every)}
+    ev = {s: (torch.cuda.Event(enable_timing=True), new_events(p))     # counted from the last step backwards
+          for s in range(args.steps) if (args.steps - 1 - s) % every == 0}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(args.steps):
